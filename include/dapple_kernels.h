@@ -1,0 +1,85 @@
+/*
+ * dapple_kernels.h -- kernel-level entry points of the stage library.
+ *
+ * The forward and backward tasks of a stage (dapple_stage.h) are sequences of the
+ * kernels below.  They are exported so that each can be checked against the CPU
+ * oracle on its own and timed on its own; they add no functionality.  All
+ * pointers are DEVICE pointers owned by the caller, `stream` is a hipStream_t
+ * (NULL = default stream), work is enqueued and not waited for, the return value
+ * is 0 or a negative STAGE_E_* code (see dapple_stage.h).
+ * dtype: 0 = fp32, 1 = bf16 storage with fp32 accumulation.
+ */
+#ifndef DAPPLE_KERNELS_H
+#define DAPPLE_KERNELS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  DAPPLE_EPI_BIAS = 1,  /* t = acc + bias[n] */
+  DAPPLE_EPI_ADD = 2,   /* t += aux[m,n]  (residual branch) */
+  DAPPLE_EPI_MUL = 4,   /* t *= aux[m,n]  (GELU' gate in the FFN backward) */
+  DAPPLE_EPI_GELU = 8,  /* C = GELU(t), C2 = GELU'(t) */
+  DAPPLE_EPI_ACC32 = 16 /* C is fp32 and C += t  (weight-gradient accumulation over
+                           micro-batches, section V-B-3 of the DAPPLE paper) */
+};
+
+/* C[m,n] = epilogue(sum_k A(m,k) B(n,k)).  A k-contiguous operand is X(r,k) =
+ * X[r*ld + k]; a k-strided one is X(r,k) = X[k*ld + r].  K may be cut in segments
+ * of kseg_len (0 = one segment): segment i reads A + i*segA, B + i*segB.  batch
+ * (0 = 1) instances at element strides sA, sB, sC, sBias.  k_valid (0 = K): rows k
+ * >= k_valid of a k-strided operand read as zero.  The linear layers of an
+ * encoder layer, their data gradients and their weight gradients are all
+ * instances of this product. */
+typedef struct {
+  const void* A;
+  const void* B;
+  void* C;
+  void* C2;
+  const void* bias;
+  const void* aux;
+  int32_t M, N, K;
+  int32_t lda, ldb, ldc, ldaux;
+  int32_t a_kstrided, b_kstrided;
+  int32_t kseg_len;
+  int64_t segA, segB;
+  int32_t batch;
+  int64_t sA, sB, sC, sBias;
+  int32_t k_valid;
+  int32_t epi;
+} dapple_gemm_desc;
+
+/* Returns 1 if the bf16 MFMA kernel takes this problem, 0 if the plain kernel does. */
+int dapple_gemm(int dtype, const dapple_gemm_desc* d, void* stream);
+
+/* Attention of one layer.  q,k,v,ctx,dctx,dq,dk,dv: [b*s, H], head h in columns
+ * [h*d, (h+1)*d), d = H / A.  lse [b,A,s] fp32: log2-domain logsumexp of the scaled
+ * logits (written by fwd, read by bwd).  delta [b,A,s] fp32: scratch of bwd.
+ * fwd: ctx = softmax(q k^T / sqrt(d)) v.  bwd: dq, dk, dv from dctx. */
+int dapple_attention_fwd(int dtype, const void* q, const void* k, const void* v, void* ctx, float* lse,
+                         int b, int s, int A, int H, void* stream);
+int dapple_attention_bwd(int dtype, const void* q, const void* k, const void* v, const void* ctx,
+                         const float* lse, const void* dctx, void* dq, void* dk, void* dv, float* delta,
+                         int b, int s, int A, int H, void* stream);
+
+/* y = LN(z) over the last dimension H (biased variance, eps inside the root);
+ * stats[2r] = mean, stats[2r+1] = 1/sqrt(var+eps). */
+int dapple_layernorm_fwd(int dtype, const void* z, const void* gamma, const void* beta, void* y,
+                         float* stats, int rows, int H, float eps, void* stream);
+/* dz from dy; dgamma += sum_r dy*xhat, dbeta += sum_r dy, dbias += sum_r dz (each
+ * fp32 [H], NULL to skip).  partial: fp32 scratch of ceil(rows/16)*3*H elements. */
+int dapple_layernorm_bwd(int dtype, const void* dy, const void* z, const float* stats, const void* gamma,
+                         void* dz, float* partial, float* dgamma, float* dbeta, float* dbias, int rows,
+                         int H, void* stream);
+/* out[c] += sum_r X[r*ld + c]; partial: fp32 scratch of ceil(rows/64)*cols elements. */
+int dapple_colsum(int dtype, const void* X, int rows, int cols, int ld, float* partial, float* out,
+                  void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

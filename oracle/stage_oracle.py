@@ -156,18 +156,35 @@ def _merge_heads(t):
     return t.transpose(0, 2, 1, 3).reshape(b, s, A * d)
 
 
+def attention_fwd(q, k, v):
+    """q, k, v [b,A,s,d] -> ctx [b,A,s,d] and P = softmax_rows(q k^T / sqrt(d)) [b,A,s,s]."""
+    d = q.shape[-1]
+    P = softmax_rows(q @ k.transpose(0, 1, 3, 2) / math.sqrt(d))
+    return P @ v, P
+
+
+def attention_bwd(dctx, q, k, v, P):
+    """Exact derivative of attention_fwd: dq, dk, dv [b,A,s,d]."""
+    d = q.shape[-1]
+    dv = P.transpose(0, 1, 3, 2) @ dctx
+    dP = dctx @ v.transpose(0, 1, 3, 2)
+    dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
+    dq = dS @ k / math.sqrt(d)
+    dk = dS.transpose(0, 1, 3, 2) @ q / math.sqrt(d)
+    return dq, dk, dv
+
+
 # --------------------------------------------------------------------------
 # one encoder layer
 # --------------------------------------------------------------------------
 
 def layer_fwd(x, p, A, eps):
     """x [b,s,H] -> y [b,s,H]; p maps the layer's parameter names to arrays."""
-    d = x.shape[-1] // A
     q = _split_heads(x @ p["Wq"] + p["bq"], A)
     k = _split_heads(x @ p["Wk"] + p["bk"], A)
     v = _split_heads(x @ p["Wv"] + p["bv"], A)
-    P = softmax_rows(q @ k.transpose(0, 1, 3, 2) / math.sqrt(d))  # [b,A,s,s]
-    ctx = _merge_heads(P @ v)
+    ctx_h, P = attention_fwd(q, k, v)
+    ctx = _merge_heads(ctx_h)
     a = ctx @ p["Wo"] + p["bo"]
     y1, ln1 = layernorm_fwd(x + a, p["ln1_g"], p["ln1_b"], eps)
     u = y1 @ p["W1"] + p["b1"]
@@ -180,8 +197,6 @@ def layer_fwd(x, p, A, eps):
 
 def layer_bwd(dy, c, p, A):
     """Exact derivative of layer_fwd: returns dx and this layer's parameter gradients."""
-    H = dy.shape[-1]
-    d = H // A
     g = {}
     flat = lambda t: t.reshape(-1, t.shape[-1])
     dz2, g["ln2_g"], g["ln2_b"] = layernorm_bwd(dy, c["ln2"], p["ln2_g"])
@@ -196,12 +211,7 @@ def layer_bwd(dy, c, p, A):
     g["Wo"] = flat(c["ctx"]).T @ flat(dz1)
     g["bo"] = flat(dz1).sum(axis=0)
     dctx = _split_heads(dz1 @ p["Wo"].T, A)                      # [b,A,s,d]
-    P = c["P"]
-    dv = P.transpose(0, 1, 3, 2) @ dctx
-    dP = dctx @ c["v"].transpose(0, 1, 3, 2)
-    dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
-    dq = dS @ c["k"] / math.sqrt(d)
-    dk = dS.transpose(0, 1, 3, 2) @ c["q"] / math.sqrt(d)
+    dq, dk, dv = attention_bwd(dctx, c["q"], c["k"], c["v"], c["P"])
     dq, dk, dv = _merge_heads(dq), _merge_heads(dk), _merge_heads(dv)
     x = c["x"]
     dx = dz1.copy()

@@ -1,0 +1,95 @@
+// Internal launcher interface between the host-side stage sequencer and the
+// gfx950 kernels.  Plain structs and pointers; every launcher enqueues on the
+// given stream and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dapple {
+
+enum Dtype { DT_F32 = 0, DT_BF16 = 1 };
+
+// ---------------------------------------------------------------- GEMM
+// C[m,n] = epilogue( sum_k A(m,k) * B(n,k) ),  m < M, n < N, k < K.
+// Operand addressing: a "k-contiguous" operand X(r,k) = X[r*ld + k]; a
+// "k-strided" operand X(r,k) = X[k*ld + r].
+// K may be cut in segments of kseg_len: segment s reads A + s*segA, B + s*segB
+// with k running inside the segment (used to contract over [dq|dk|dv] held in
+// three separate buffers).  batch: grid.z instances at strides sA, sB, sC, sBias.
+enum GemmEpi {
+  EPI_BIAS = 1,   // t = acc + bias[n]
+  EPI_ADD = 2,    // t += aux[m,n]
+  EPI_MUL = 4,    // t *= aux[m,n]
+  EPI_GELU = 8,   // C = gelu(t), C2 = gelu'(t)
+  EPI_ACC32 = 16  // C is fp32 and C += t (weight-gradient accumulation)
+};
+
+struct GemmArgs {
+  const void* A;
+  const void* B;
+  void* C;
+  void* C2;
+  const void* bias;
+  const void* aux;
+  int M, N, K;
+  int lda, ldb, ldc, ldaux;
+  int a_kstrided, b_kstrided;
+  int kseg_len;
+  long segA, segB;
+  int batch;
+  long sA, sB, sC, sBias;
+  int k_valid;  // k-strided operands: rows k >= k_valid read as zero (K itself is padded)
+  int epi;
+};
+
+hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st);
+// true when the MFMA kernel takes this problem (else the plain ALU kernel does)
+bool gemm_uses_mfma(Dtype dt, const GemmArgs& g);
+
+// ---------------------------------------------------------------- attention
+// q,k,v,ctx,dq,dk,dv,dctx: [b*s, H] row-major, head h in columns [h*d, (h+1)*d).
+// lse: [b, A, s] fp32, log2-domain logsumexp of the scaled logits.
+// delta: [b, A, s] fp32 scratch, rowsum(dctx * ctx) per head.
+struct AttnArgs {
+  const void *q, *k, *v;
+  void* ctx;
+  float* lse;
+  const void* dctx;
+  void *dq, *dk, *dv;
+  float* delta;
+  int b, s, A, d, H;
+};
+hipError_t launch_attn_fwd(Dtype dt, const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_bwd(Dtype dt, const AttnArgs& a, hipStream_t st);
+bool attn_uses_mfma(Dtype dt, const AttnArgs& a);
+
+// ---------------------------------------------------------------- row kernels
+// y = LN(z) over the last dim (H), stats[2*r] = mean, stats[2*r+1] = rstd.
+hipError_t launch_ln_fwd(Dtype dt, const void* z, const void* gamma, const void* beta, void* y,
+                         float* stats, int rows, int H, float eps, hipStream_t st);
+// dz = LN backward; partial[(blk*3 + {0,1,2})*H + c] = block partial sums of
+// dy*xhat (dgamma), dy (dbeta), dz (bias of the linear that produced z).
+// Returns the number of partial blocks through *nblk.
+hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, const float* stats,
+                         const void* gamma, void* dz, float* partial, int* nblk, int rows, int H,
+                         hipStream_t st);
+// o_v[c] += sum over blk (ascending) of partial[(blk*nvec + v)*H + c], v < nvec <= 3;
+// a NULL o_v is skipped
+hipError_t launch_partial_reduce(const float* partial, int nblk, int nvec, int H, float* o0,
+                                 float* o1, float* o2, hipStream_t st);
+// out[c] += sum_r X[r*ld + c]  (two fixed-order stages through `partial`)
+hipError_t launch_colsum(Dtype dt, const void* X, int rows, int cols, int ld, float* partial,
+                         float* out, hipStream_t st);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+hipError_t launch_zero(void* dst, size_t bytes, hipStream_t st);
+
+// ---------------------------------------------------------------- embedding / head
+// e[r] = E_w[ids[r]] + E_p[r % s]
+hipError_t launch_embed_gather(Dtype dt, const int32_t* ids, const void* Ew, const void* Ep, void* e,
+                               int rows, int s, int H, hipStream_t st);
+// dEw[id] += sum over rows r with ids[r] == id (ascending r) of de[r];
+// dEp[p] += sum over sequences of de[bi*s + p]
+hipError_t launch_embed_bwd(Dtype dt, const int32_t* ids, const void* de, float* dEw, float* dEp,
+                            int rows, int s, int H, int vocab, int32_t* scratch, hipStream_t st);
+
+}  // namespace dapple

@@ -1,0 +1,338 @@
+// Row-wise kernels: LayerNorm forward / backward, column sums for bias gradients,
+// fixed-order partial reductions, copy and zero fill.  All are HBM-bound: one
+// wave per row with 16-byte accesses, fp32 arithmetic, and every cross-row sum is
+// taken in a fixed order (per-block partial sums, then an ascending sum over
+// blocks) so that results do not depend on timing.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace dapple {
+
+template <typename T> struct Vec;
+template <> struct Vec<float> { static constexpr int N = 4; };
+template <> struct Vec<bf16> { static constexpr int N = 8; };
+
+template <typename T>
+__device__ __forceinline__ void load_vec(const T* p, float (&o)[Vec<T>::N]);
+template <>
+__device__ __forceinline__ void load_vec<float>(const float* p, float (&o)[4]) {
+  float4 v = *(const float4*)p;
+  o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+}
+template <>
+__device__ __forceinline__ void load_vec<bf16>(const bf16* p, float (&o)[8]) {
+  bf16x8 v = *(const bf16x8*)p;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (float)v[e];
+}
+template <typename T>
+__device__ __forceinline__ void store_vec(T* p, const float (&o)[Vec<T>::N]);
+template <>
+__device__ __forceinline__ void store_vec<float>(float* p, const float (&o)[4]) {
+  *(float4*)p = make_float4(o[0], o[1], o[2], o[3]);
+}
+template <>
+__device__ __forceinline__ void store_vec<bf16>(bf16* p, const float (&o)[8]) {
+  bf16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (bf16)o[e];
+  *(bf16x8*)p = v;
+}
+
+// ------------------------------------------------------------------ LayerNorm forward
+// one wave per row; NCH = ceil(H / (64 * VEC)) register chunks per lane
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ z, const T* __restrict__ gamma,
+                                                     const T* __restrict__ beta, T* __restrict__ y,
+                                                     float* __restrict__ stats, int rows, int H, float eps) {
+  constexpr int V = Vec<T>::N;
+  int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* zr = z + (long)row * H;
+  float x[NCH][V];
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    int col = (c * 64 + lane) * V;
+    if (col < H) {
+      load_vec<T>(zr + col, x[c]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) s += x[c][e];
+    }
+  }
+  float mean = wave_sum(s) / (float)H;
+  float q = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    int col = (c * 64 + lane) * V;
+    if (col < H) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        float d = x[c][e] - mean;
+        q += d * d;
+      }
+    }
+  }
+  float rstd = rsqrtf(wave_sum(q) / (float)H + eps);
+  if (lane == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    int col = (c * 64 + lane) * V;
+    if (col < H) {
+      float g[V], b[V], o[V];
+      load_vec<T>(gamma + col, g);
+      load_vec<T>(beta + col, b);
+#pragma unroll
+      for (int e = 0; e < V; ++e) o[e] = (x[c][e] - mean) * rstd * g[e] + b[e];
+      store_vec<T>(y + (long)row * H + col, o);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ LayerNorm backward
+// A block takes LNB_ROWS consecutive rows (each wave every 4th of them), keeps the
+// per-column partial sums of dy*xhat, dy and dz in registers, combines the four
+// waves in LDS in wave order and writes partial[(blk*3 + v)*H + col].
+constexpr int LNB_ROWS = 16;
+
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ z,
+                                                     const float* __restrict__ stats, const T* __restrict__ gamma,
+                                                     T* __restrict__ dz, float* __restrict__ partial, int rows, int H) {
+  constexpr int V = Vec<T>::N;
+  extern __shared__ float red[];  // [3][H]
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float pg[NCH][V], pb[NCH][V], pz[NCH][V], g[NCH][V];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    int col = (c * 64 + lane) * V;
+#pragma unroll
+    for (int e = 0; e < V; ++e) pg[c][e] = pb[c][e] = pz[c][e] = g[c][e] = 0.f;
+    if (col < H) load_vec<T>(gamma + col, g[c]);
+  }
+  for (int rr = wave; rr < LNB_ROWS; rr += 4) {
+    int row = blockIdx.x * LNB_ROWS + rr;
+    if (row >= rows) break;
+    float mean = stats[2 * row], rstd = stats[2 * row + 1];
+    float d[NCH][V], xh[NCH][V];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      int col = (c * 64 + lane) * V;
+      if (col < H) {
+        float zz[V];
+        load_vec<T>(dy + (long)row * H + col, d[c]);
+        load_vec<T>(z + (long)row * H + col, zz);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          xh[c][e] = (zz[e] - mean) * rstd;
+          float dxh = d[c][e] * g[c][e];
+          s1 += dxh;
+          s2 += dxh * xh[c][e];
+        }
+      }
+    }
+    float m1 = wave_sum(s1) / (float)H, m2 = wave_sum(s2) / (float)H;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      int col = (c * 64 + lane) * V;
+      if (col < H) {
+        float o[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          o[e] = rstd * (d[c][e] * g[c][e] - m1 - xh[c][e] * m2);
+          pg[c][e] += d[c][e] * xh[c][e];
+          pb[c][e] += d[c][e];
+        }
+        store_vec<T>(dz + (long)row * H + col, o);
+        // the bias gradient of the producing linear sums dz as it is stored
+#pragma unroll
+        for (int e = 0; e < V; ++e) pz[c][e] += to_f32(from_f32<T>(o[e]));
+      }
+    }
+  }
+  // combine the four waves in wave order: ((w0 + w1) + w2) + w3
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        int col = (c * 64 + lane) * V;
+        if (col < H) {
+#pragma unroll
+          for (int e = 0; e < V; ++e) {
+            if (w == 0) {
+              red[0 * H + col + e] = pg[c][e];
+              red[1 * H + col + e] = pb[c][e];
+              red[2 * H + col + e] = pz[c][e];
+            } else {
+              red[0 * H + col + e] += pg[c][e];
+              red[1 * H + col + e] += pb[c][e];
+              red[2 * H + col + e] += pz[c][e];
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  for (int i = threadIdx.x; i < 3 * H; i += 256) partial[(long)blockIdx.x * 3 * H + i] = red[i];
+}
+
+// out_v[c] += sum_{blk ascending} partial[(blk*nvec + v)*H + c]
+__global__ void partial_reduce_kernel(const float* __restrict__ partial, int nblk, int nvec, int H, float* o0,
+                                      float* o1, float* o2) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  int v = blockIdx.y;
+  if (c >= H) return;
+  float* o = v == 0 ? o0 : (v == 1 ? o1 : o2);
+  if (!o) return;
+  float t = 0.f;
+  for (int b = 0; b < nblk; ++b) t += partial[((long)b * nvec + v) * H + c];
+  o[c] += t;
+}
+
+// ------------------------------------------------------------------ column sums
+constexpr int CS_ROWS = 64;
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, int rows, int cols, int ld,
+                                                     float* __restrict__ partial) {
+  constexpr int V = Vec<T>::N;
+  __shared__ float red[4][64 * V];
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int col = (blockIdx.x * 64 + lane) * V;
+  float acc[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.f;
+  if (col < cols) {
+    int r0 = blockIdx.y * CS_ROWS;
+    for (int rr = wave; rr < CS_ROWS; rr += 4) {
+      int row = r0 + rr;
+      if (row >= rows) break;
+      float x[V];
+      load_vec<T>(X + (long)row * ld + col, x);
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] += x[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < V; ++e) red[wave][lane * V + e] = acc[e];
+  __syncthreads();
+  if (wave == 0 && col < cols) {
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      float t = red[0][lane * V + e] + red[1][lane * V + e];
+      t += red[2][lane * V + e];
+      t += red[3][lane * V + e];
+      partial[(long)blockIdx.y * cols + col + e] = t;
+    }
+  }
+}
+
+__global__ void zero_kernel(uint4* p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+__global__ void copy_kernel(uint4* d, const uint4* s, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) d[i] = s[i];
+}
+
+// ------------------------------------------------------------------ launchers
+template <typename T>
+static int nch_for(int H) {
+  int per = 64 * Vec<T>::N;
+  return (H + per - 1) / per;
+}
+
+template <typename T>
+static hipError_t ln_fwd_t(const void* z, const void* g, const void* b, void* y, float* stats, int rows, int H,
+                           float eps, hipStream_t st) {
+  dim3 grid((rows + 3) / 4), blk(256);
+  int n = nch_for<T>(H);
+#define LNF(N)                                                                                              \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, N>), grid, blk, 0, st, (const T*)z, (const T*)g, (const T*)b, (T*)y, \
+                     stats, rows, H, eps)
+  if (n <= 1) LNF(1);
+  else if (n <= 2) LNF(2);
+  else if (n <= 4) LNF(4);
+  else if (n <= 8) LNF(8);
+  else return hipErrorInvalidValue;
+#undef LNF
+  return hipGetLastError();
+}
+
+hipError_t launch_ln_fwd(Dtype dt, const void* z, const void* gamma, const void* beta, void* y, float* stats,
+                         int rows, int H, float eps, hipStream_t st) {
+  return dt == DT_BF16 ? ln_fwd_t<bf16>(z, gamma, beta, y, stats, rows, H, eps, st)
+                       : ln_fwd_t<float>(z, gamma, beta, y, stats, rows, H, eps, st);
+}
+
+template <typename T>
+static hipError_t ln_bwd_t(const void* dy, const void* z, const float* stats, const void* g, void* dz,
+                           float* partial, int nb, int rows, int H, hipStream_t st) {
+  dim3 grid(nb), blk(256);
+  size_t sh = (size_t)3 * H * sizeof(float);
+  int n = nch_for<T>(H);
+#define LNB(N)                                                                                                 \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, N>), grid, blk, sh, st, (const T*)dy, (const T*)z, stats, (const T*)g, \
+                     (T*)dz, partial, rows, H)
+  if (n <= 1) LNB(1);
+  else if (n <= 2) LNB(2);
+  else if (n <= 4) LNB(4);
+  else return hipErrorInvalidValue;
+#undef LNB
+  return hipGetLastError();
+}
+
+hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, const float* stats, const void* gamma, void* dz,
+                         float* partial, int* nblk, int rows, int H, hipStream_t st) {
+  int nb = (rows + LNB_ROWS - 1) / LNB_ROWS;
+  *nblk = nb;
+  return dt == DT_BF16 ? ln_bwd_t<bf16>(dy, z, stats, gamma, dz, partial, nb, rows, H, st)
+                       : ln_bwd_t<float>(dy, z, stats, gamma, dz, partial, nb, rows, H, st);
+}
+
+hipError_t launch_partial_reduce(const float* partial, int nblk, int nvec, int H, float* o0, float* o1, float* o2,
+                                 hipStream_t st) {
+  dim3 grid((H + 255) / 256, nvec), blk(256);
+  hipLaunchKernelGGL(partial_reduce_kernel, grid, blk, 0, st, partial, nblk, nvec, H, o0, o1, o2);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum(Dtype dt, const void* X, int rows, int cols, int ld, float* partial, float* out,
+                         hipStream_t st) {
+  int nrb = (rows + CS_ROWS - 1) / CS_ROWS;
+  if (dt == DT_BF16) {
+    dim3 grid((cols + 64 * 8 - 1) / (64 * 8), nrb);
+    hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, rows, cols, ld, partial);
+  } else {
+    dim3 grid((cols + 64 * 4 - 1) / (64 * 4), nrb);
+    hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, rows, cols, ld, partial);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_partial_reduce(partial, nrb, 1, cols, out, nullptr, nullptr, st);
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+  size_t n16 = bytes / 16;
+  if (!n16) return hipSuccess;
+  int blocks = (int)((n16 + 255) / 256 < 2048 ? (n16 + 255) / 256 : 2048);
+  hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, st, (uint4*)dst, (const uint4*)src, n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_zero(void* dst, size_t bytes, hipStream_t st) {
+  size_t n16 = bytes / 16;
+  if (!n16) return hipSuccess;
+  int blocks = (int)((n16 + 255) / 256 < 2048 ? (n16 + 255) / 256 : 2048);
+  hipLaunchKernelGGL(zero_kernel, dim3(blocks), dim3(256), 0, st, (uint4*)dst, n16);
+  return hipGetLastError();
+}
+
+}  // namespace dapple

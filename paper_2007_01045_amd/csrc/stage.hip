@@ -1,0 +1,600 @@
+// Host side of the stage library: configuration checks, arena layout, the bounded
+// activation-slot allocator, the schedule generator / validator / executor, the
+// per-task kernel sequences, and the C ABI declared in dapple_stage.h.
+//
+// Nothing here touches tensor values: every step of a task is one of the kernels
+// in gemm.hip, attention.hip, rowops.hip, embed_head.hip.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/dapple_stage.h"
+#include "kernels.h"
+
+using namespace dapple;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+enum KClass {
+  KC_GEMM_FWD = 0, KC_GEMM_DGRAD, KC_GEMM_WGRAD, KC_ATTN_FWD, KC_ATTN_BWD, KC_LN_FWD, KC_LN_BWD,
+  KC_REDUCE, KC_COPY, KC_EMBED, KC_HEAD, KC_COUNT
+};
+const char* const kClassNames[KC_COUNT] = {"gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd",
+                                           "ln_bwd",   "reduce",     "copy_zero",  "embed",    "head"};
+
+// element offsets of one layer's tensors in the flat parameter vector
+struct LayerParams {
+  size_t Wq, bq, Wk, bk, Wv, bv, Wo, bo, ln1g, ln1b, W1, b1, W2, b2, ln2g, ln2b;
+};
+// byte offsets of one layer's stash inside an activation slot
+struct LayerStash {
+  size_t qkv, lse, ctx, z1, st1, y1, gp, g, z2, st2, y;
+};
+
+struct Layout {
+  // parameters
+  size_t n_params = 0;
+  size_t embEw = 0, embEp = 0, embG = 0, embB = 0;
+  std::vector<LayerParams> lp;
+  size_t hWt = 0, hbt = 0, hG = 0, hB = 0, hEout = 0, hbout = 0;
+  // slot
+  size_t slot_x0 = 0, slot_ids = 0, slot_embsum = 0, slot_embst = 0;
+  std::vector<LayerStash> ls;
+  size_t slot_head = 0;
+  size_t slot_bytes = 0;
+  // workspace (bytes)
+  size_t ws_dx[2] = {0, 0}, ws_dz2 = 0, ws_du = 0, ws_dy1 = 0, ws_dz1 = 0, ws_dctx = 0, ws_dqkv = 0, ws_delta = 0,
+         ws_partial = 0, ws_head = 0;
+  size_t workspace_bytes = 0;
+  // arena
+  size_t grad_bytes = 0, arena_grads = 0, arena_slots = 0, arena_ws = 0, arena_bytes = 0;
+};
+
+int check_config(const stage_config& c) {
+  if (c.n_layers < 1 || c.hidden < 1 || c.n_heads < 1 || c.ffn < 1 || c.seq < 1 || c.micro_batch < 1)
+    return fail(STAGE_E_CONFIG, "n_layers, hidden, n_heads, ffn, seq, micro_batch must be positive");
+  if (c.hidden % c.n_heads) return fail(STAGE_E_CONFIG, "hidden (%d) is not a multiple of n_heads (%d)", c.hidden, c.n_heads);
+  if (c.max_slots < 1) return fail(STAGE_E_CONFIG, "max_slots must be at least 1");
+  if (c.dtype != STAGE_DTYPE_F32 && c.dtype != STAGE_DTYPE_BF16) return fail(STAGE_E_CONFIG, "unknown dtype %d", c.dtype);
+  int vec = c.dtype == STAGE_DTYPE_BF16 ? 8 : 4;
+  if (c.hidden % vec || c.ffn % vec)
+    return fail(STAGE_E_CONFIG, "hidden and ffn must be multiples of %d for this dtype", vec);
+  if (c.hidden > 64 * vec * 4) return fail(STAGE_E_CONFIG, "hidden larger than %d is not supported", 64 * vec * 4);
+  if (!(c.ln_eps >= 0.f)) return fail(STAGE_E_CONFIG, "ln_eps must be non-negative");
+  if (c.has_embedding && c.has_mlm_head)
+    return fail(STAGE_E_CONFIG, "a stage has the embedding block or the MLM head, not both");
+  if (c.has_embedding || c.has_mlm_head) {
+    if (c.vocab < 1) return fail(STAGE_E_CONFIG, "vocab must be positive");
+    if (c.has_embedding && c.max_pos < c.seq) return fail(STAGE_E_CONFIG, "max_pos (%d) smaller than seq (%d)", c.max_pos, c.seq);
+  }
+  if ((long)c.micro_batch * c.seq > (1 << 24)) return fail(STAGE_E_CONFIG, "micro_batch * seq too large");
+  return STAGE_OK;
+}
+
+void build_layout(const stage_config& c, Layout& L) {
+  const size_t H = c.hidden, F = c.ffn, T = (size_t)c.micro_batch * c.seq, E = c.dtype == STAGE_DTYPE_BF16 ? 2 : 4;
+  const size_t V = c.vocab, P = c.max_pos;
+  size_t off = 0;
+  auto take = [&](size_t n) { size_t o = off; off += n; return o; };
+  if (c.has_embedding) {
+    L.embEw = take(V * H); L.embEp = take(P * H); L.embG = take(H); L.embB = take(H);
+  }
+  L.lp.resize(c.n_layers);
+  for (auto& p : L.lp) {
+    p.Wq = take(H * H); p.bq = take(H); p.Wk = take(H * H); p.bk = take(H); p.Wv = take(H * H); p.bv = take(H);
+    p.Wo = take(H * H); p.bo = take(H); p.ln1g = take(H); p.ln1b = take(H);
+    p.W1 = take(H * F); p.b1 = take(F); p.W2 = take(F * H); p.b2 = take(H); p.ln2g = take(H); p.ln2b = take(H);
+  }
+  if (c.has_mlm_head) {
+    L.hWt = take(H * H); L.hbt = take(H); L.hG = take(H); L.hB = take(H); L.hEout = take(V * H); L.hbout = take(V);
+  }
+  L.n_params = off;
+
+  // activation slot: what F_m leaves for B_m
+  size_t so = 0;
+  auto stake = [&](size_t bytes) { size_t o = so; so += align_up(bytes); return o; };
+  const size_t U = T * H * E;
+  if (c.has_embedding) {
+    L.slot_ids = stake(T * 4); L.slot_embsum = stake(U); L.slot_embst = stake(2 * T * 4);
+  }
+  L.slot_x0 = stake(U);
+  L.ls.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    auto& s = L.ls[l];
+    s.qkv = stake(3 * U);   // q, k, v contiguous (3U is a multiple of 256 whenever U is)
+    s.lse = stake((size_t)c.micro_batch * c.n_heads * c.seq * 4);
+    s.ctx = stake(U); s.z1 = stake(U); s.st1 = stake(2 * T * 4); s.y1 = stake(U);
+    s.gp = stake(T * F * E); s.g = stake(T * F * E); s.z2 = stake(U); s.st2 = stake(2 * T * 4);
+    bool keep_y = l + 1 < c.n_layers || c.has_mlm_head;
+    s.y = keep_y ? stake(U) : 0;
+  }
+  L.slot_bytes = so;
+
+  size_t wo = 0;
+  auto wtake = [&](size_t bytes) { size_t o = wo; wo += align_up(bytes); return o; };
+  L.ws_dx[0] = wtake(U); L.ws_dx[1] = wtake(U); L.ws_dz2 = wtake(U); L.ws_du = wtake(T * F * E);
+  L.ws_dy1 = wtake(U); L.ws_dz1 = wtake(U); L.ws_dctx = wtake(U); L.ws_dqkv = wtake(3 * U);
+  L.ws_delta = wtake((size_t)c.micro_batch * c.n_heads * c.seq * 4);
+  size_t ln_part = ((T + 15) / 16) * 3 * H * 4, cs_part = ((T + 63) / 64) * (F > H ? F : H) * 4;
+  L.ws_partial = wtake(ln_part > cs_part ? ln_part : cs_part);
+  L.workspace_bytes = wo;
+
+  L.grad_bytes = align_up(L.n_params * 4);
+  L.arena_grads = 0;
+  L.arena_slots = L.grad_bytes;
+  L.arena_ws = L.arena_slots + (size_t)c.max_slots * L.slot_bytes;
+  L.arena_bytes = L.arena_ws + L.workspace_bytes;
+}
+
+struct ProfEvent { hipEvent_t a, b; int cls; double flops; };
+
+}  // namespace
+
+struct dapple_stage {
+  stage_config cfg;
+  Layout L;
+  Dtype dt;
+  bool dry;
+  const char* W;   // parameters (device, caller-owned)
+  char* arena;
+  float* grads;
+  hipStream_t st;
+  std::vector<int> slot_of_mb;   // slot -> micro-batch id, -1 = free
+  int live = 0, peak_live = 0;
+  uint64_t fwd_tasks = 0, bwd_tasks = 0, launches = 0;
+  bool profiling = false;
+  std::vector<ProfEvent> events;
+  size_t events_used = 0;
+
+  size_t E() const { return cfg.dtype == STAGE_DTYPE_BF16 ? 2 : 4; }
+  const char* w(size_t elem_off) const { return W + elem_off * E(); }
+  float* gr(size_t elem_off) const { return grads + elem_off; }
+  char* slot(int s) const { return arena + L.arena_slots + (size_t)s * L.slot_bytes; }
+  char* ws(size_t off) const { return arena + L.arena_ws + off; }
+
+  // run one launcher; with profiling on, bracket it with two events
+  template <typename Fn>
+  int run(int cls, double flops, Fn&& fn) {
+    if (dry) { ++launches; return STAGE_OK; }
+    ProfEvent* pe = nullptr;
+    if (profiling) {
+      if (events_used == events.size()) {
+        ProfEvent e{};
+        if (hipEventCreate(&e.a) != hipSuccess || hipEventCreate(&e.b) != hipSuccess)
+          return fail(STAGE_E_DEVICE, "hipEventCreate failed");
+        events.push_back(e);
+      }
+      pe = &events[events_used++];
+      pe->cls = cls; pe->flops = flops;
+      (void)hipEventRecord(pe->a, st);
+    }
+    hipError_t e = fn();
+    if (pe) (void)hipEventRecord(pe->b, st);
+    ++launches;
+    if (e != hipSuccess) return fail(STAGE_E_DEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+    return STAGE_OK;
+  }
+
+  int gemm(int cls, GemmArgs g) {
+    if (g.kseg_len == 0) g.kseg_len = g.K;
+    if (g.k_valid == 0) g.k_valid = g.K;
+    if (g.batch == 0) g.batch = 1;
+    double flops = 2.0 * g.M * g.N * (double)g.K * g.batch;
+    return run(cls, flops, [&] { return launch_gemm(dt, g, st); });
+  }
+
+  int forward(int s, const void* x, void* y, const void* aux);
+  int backward(int s, const void* dy, void* dx);
+};
+
+#define TRY(expr) do { int rc_ = (expr); if (rc_ != STAGE_OK) return rc_; } while (0)
+
+int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
+  const int H = cfg.hidden, F = cfg.ffn, T = cfg.micro_batch * cfg.seq;
+  const size_t U = (size_t)T * H * E();
+  char* sl = slot(s);
+  (void)aux;
+  const char* xin = sl + L.slot_x0;
+  TRY(run(KC_COPY, 0, [&] { return launch_copy(sl + L.slot_x0, x, U, st); }));
+  for (int l = 0; l < cfg.n_layers; ++l) {
+    const LayerParams& p = L.lp[l];
+    const LayerStash& a = L.ls[l];
+    char *qkv = sl + a.qkv, *ctx = sl + a.ctx, *z1 = sl + a.z1, *y1 = sl + a.y1, *gp = sl + a.gp, *g = sl + a.g,
+         *z2 = sl + a.z2;
+    float *lse = (float*)(sl + a.lse), *st1 = (float*)(sl + a.st1), *st2 = (float*)(sl + a.st2);
+    char* yout = (l + 1 < cfg.n_layers || cfg.has_mlm_head) ? sl + a.y : (char*)y;
+    {  // q, k, v = x Wq + bq, x Wk + bk, x Wv + bv  (three products in one launch)
+      GemmArgs ga{};
+      ga.A = xin; ga.lda = H; ga.B = w(p.Wq); ga.ldb = H; ga.b_kstrided = 1; ga.bias = w(p.bq);
+      ga.C = qkv; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H; ga.batch = 3;
+      ga.sA = 0; ga.sB = (long)H * H + H; ga.sBias = (long)H * H + H; ga.sC = (long)T * H; ga.epi = EPI_BIAS;
+      TRY(gemm(KC_GEMM_FWD, ga));
+    }
+    {
+      AttnArgs aa{};
+      aa.q = qkv; aa.k = qkv + U; aa.v = qkv + 2 * U; aa.ctx = ctx; aa.lse = lse;
+      aa.b = cfg.micro_batch; aa.s = cfg.seq; aa.A = cfg.n_heads; aa.d = H / cfg.n_heads; aa.H = H;
+      double fl = 4.0 * T * (double)cfg.seq * H;
+      TRY(run(KC_ATTN_FWD, fl, [&] { return launch_attn_fwd(dt, aa, st); }));
+    }
+    {  // z1 = x + ctx Wo + bo
+      GemmArgs ga{};
+      ga.A = ctx; ga.lda = H; ga.B = w(p.Wo); ga.ldb = H; ga.b_kstrided = 1; ga.bias = w(p.bo);
+      ga.aux = xin; ga.ldaux = H; ga.C = z1; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H; ga.epi = EPI_BIAS | EPI_ADD;
+      TRY(gemm(KC_GEMM_FWD, ga));
+    }
+    TRY(run(KC_LN_FWD, 0, [&] { return launch_ln_fwd(dt, z1, w(p.ln1g), w(p.ln1b), y1, st1, T, H, cfg.ln_eps, st); }));
+    {  // g = GELU(y1 W1 + b1), gp = GELU'(y1 W1 + b1)
+      GemmArgs ga{};
+      ga.A = y1; ga.lda = H; ga.B = w(p.W1); ga.ldb = F; ga.b_kstrided = 1; ga.bias = w(p.b1);
+      ga.C = g; ga.C2 = gp; ga.ldc = F; ga.M = T; ga.N = F; ga.K = H; ga.epi = EPI_BIAS | EPI_GELU;
+      TRY(gemm(KC_GEMM_FWD, ga));
+    }
+    {  // z2 = y1 + g W2 + b2
+      GemmArgs ga{};
+      ga.A = g; ga.lda = F; ga.B = w(p.W2); ga.ldb = H; ga.b_kstrided = 1; ga.bias = w(p.b2);
+      ga.aux = y1; ga.ldaux = H; ga.C = z2; ga.ldc = H; ga.M = T; ga.N = H; ga.K = F; ga.epi = EPI_BIAS | EPI_ADD;
+      TRY(gemm(KC_GEMM_FWD, ga));
+    }
+    TRY(run(KC_LN_FWD, 0, [&] { return launch_ln_fwd(dt, z2, w(p.ln2g), w(p.ln2b), yout, st2, T, H, cfg.ln_eps, st); }));
+    xin = yout;
+  }
+  return STAGE_OK;
+}
+
+int dapple_stage::backward(int s, const void* dy, void* dx) {
+  const int H = cfg.hidden, F = cfg.ffn, T = cfg.micro_batch * cfg.seq;
+  const size_t U = (size_t)T * H * E();
+  char* sl = slot(s);
+  char *dz2 = ws(L.ws_dz2), *du = ws(L.ws_du), *dy1 = ws(L.ws_dy1), *dz1 = ws(L.ws_dz1), *dctx = ws(L.ws_dctx),
+       *dqkv = ws(L.ws_dqkv);
+  float *delta = (float*)ws(L.ws_delta), *partial = (float*)ws(L.ws_partial);
+  const char* dyin = (const char*)dy;
+  for (int l = cfg.n_layers - 1; l >= 0; --l) {
+    const LayerParams& p = L.lp[l];
+    const LayerStash& a = L.ls[l];
+    const char* xl = l == 0 ? sl + L.slot_x0 : sl + L.ls[l - 1].y;
+    char *qkv = sl + a.qkv, *ctx = sl + a.ctx, *z1 = sl + a.z1, *y1 = sl + a.y1, *gp = sl + a.gp, *g = sl + a.g,
+         *z2 = sl + a.z2;
+    float *lse = (float*)(sl + a.lse), *st1 = (float*)(sl + a.st1), *st2 = (float*)(sl + a.st2);
+    char* dxout = l == 0 ? (char*)dx : ws(L.ws_dx[l & 1]);
+    int nblk = 0;
+    // y = LN(z2): dz2, and the gradients of ln2 gain/shift and of b2
+    TRY(run(KC_LN_BWD, 0, [&] { return launch_ln_bwd(dt, dyin, z2, st2, w(p.ln2g), dz2, partial, &nblk, T, H, st); }));
+    TRY(run(KC_REDUCE, 0, [&] { return launch_partial_reduce(partial, (T + 15) / 16, 3, H, gr(p.ln2g), gr(p.ln2b), gr(p.b2), st); }));
+    {  // dW2 += g^T dz2
+      GemmArgs ga{};
+      ga.A = g; ga.lda = F; ga.a_kstrided = 1; ga.B = dz2; ga.ldb = H; ga.b_kstrided = 1;
+      ga.C = gr(p.W2); ga.ldc = H; ga.M = F; ga.N = H; ga.K = T; ga.epi = EPI_ACC32;
+      TRY(gemm(KC_GEMM_WGRAD, ga));
+    }
+    {  // du = (dz2 W2^T) o GELU'(u)
+      GemmArgs ga{};
+      ga.A = dz2; ga.lda = H; ga.B = w(p.W2); ga.ldb = H; ga.aux = gp; ga.ldaux = F;
+      ga.C = du; ga.ldc = F; ga.M = T; ga.N = F; ga.K = H; ga.epi = EPI_MUL;
+      TRY(gemm(KC_GEMM_DGRAD, ga));
+    }
+    TRY(run(KC_REDUCE, 0, [&] { return launch_colsum(dt, du, T, F, F, partial, gr(p.b1), st); }));
+    {  // dW1 += y1^T du
+      GemmArgs ga{};
+      ga.A = y1; ga.lda = H; ga.a_kstrided = 1; ga.B = du; ga.ldb = F; ga.b_kstrided = 1;
+      ga.C = gr(p.W1); ga.ldc = F; ga.M = H; ga.N = F; ga.K = T; ga.epi = EPI_ACC32;
+      TRY(gemm(KC_GEMM_WGRAD, ga));
+    }
+    {  // dy1 = du W1^T + dz2 (residual branch)
+      GemmArgs ga{};
+      ga.A = du; ga.lda = F; ga.B = w(p.W1); ga.ldb = F; ga.aux = dz2; ga.ldaux = H;
+      ga.C = dy1; ga.ldc = H; ga.M = T; ga.N = H; ga.K = F; ga.epi = EPI_ADD;
+      TRY(gemm(KC_GEMM_DGRAD, ga));
+    }
+    TRY(run(KC_LN_BWD, 0, [&] { return launch_ln_bwd(dt, dy1, z1, st1, w(p.ln1g), dz1, partial, &nblk, T, H, st); }));
+    TRY(run(KC_REDUCE, 0, [&] { return launch_partial_reduce(partial, (T + 15) / 16, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), st); }));
+    {  // dWo += ctx^T dz1
+      GemmArgs ga{};
+      ga.A = ctx; ga.lda = H; ga.a_kstrided = 1; ga.B = dz1; ga.ldb = H; ga.b_kstrided = 1;
+      ga.C = gr(p.Wo); ga.ldc = H; ga.M = H; ga.N = H; ga.K = T; ga.epi = EPI_ACC32;
+      TRY(gemm(KC_GEMM_WGRAD, ga));
+    }
+    {  // dctx = dz1 Wo^T
+      GemmArgs ga{};
+      ga.A = dz1; ga.lda = H; ga.B = w(p.Wo); ga.ldb = H; ga.C = dctx; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H;
+      TRY(gemm(KC_GEMM_DGRAD, ga));
+    }
+    {
+      AttnArgs aa{};
+      aa.q = qkv; aa.k = qkv + U; aa.v = qkv + 2 * U; aa.ctx = ctx; aa.lse = lse; aa.dctx = dctx;
+      aa.dq = dqkv; aa.dk = dqkv + U; aa.dv = dqkv + 2 * U; aa.delta = delta;
+      aa.b = cfg.micro_batch; aa.s = cfg.seq; aa.A = cfg.n_heads; aa.d = H / cfg.n_heads; aa.H = H;
+      double fl = 8.0 * T * (double)cfg.seq * H;
+      TRY(run(KC_ATTN_BWD, fl, [&] { return launch_attn_bwd(dt, aa, st); }));
+    }
+    const size_t pstride = (size_t)H * H + H;
+    for (int z = 0; z < 3; ++z)
+      TRY(run(KC_REDUCE, 0, [&] { return launch_colsum(dt, dqkv + z * U, T, H, H, partial, gr(p.bq + z * pstride), st); }));
+    {  // dWq, dWk, dWv += x^T dq, x^T dk, x^T dv
+      GemmArgs ga{};
+      ga.A = xl; ga.lda = H; ga.a_kstrided = 1; ga.B = dqkv; ga.ldb = H; ga.b_kstrided = 1;
+      ga.C = gr(p.Wq); ga.ldc = H; ga.M = H; ga.N = H; ga.K = T; ga.batch = 3;
+      ga.sA = 0; ga.sB = (long)T * H; ga.sC = (long)pstride; ga.epi = EPI_ACC32;
+      TRY(gemm(KC_GEMM_WGRAD, ga));
+    }
+    {  // dx = dq Wq^T + dk Wk^T + dv Wv^T + dz1 (residual branch): one product over K = 3H
+      GemmArgs ga{};
+      ga.A = dqkv; ga.lda = H; ga.B = w(p.Wq); ga.ldb = H; ga.aux = dz1; ga.ldaux = H;
+      ga.C = dxout; ga.ldc = H; ga.M = T; ga.N = H; ga.K = 3 * H; ga.kseg_len = H;
+      ga.segA = (long)T * H; ga.segB = (long)pstride; ga.epi = EPI_ADD;
+      TRY(gemm(KC_GEMM_DGRAD, ga));
+    }
+    dyin = dxout;
+  }
+  return STAGE_OK;
+}
+
+// ------------------------------------------------------------------ schedule
+static int make_schedule(int M, int K, int order, std::vector<int32_t>& ops) {
+  if (M < 1 || K < 1) return fail(STAGE_E_BAD_ORDER, "M and K must be positive (M=%d, K=%d)", M, K);
+  ops.clear();
+  if (order == STAGE_ORDER_GPIPE) {
+    for (int m = 0; m < M; ++m) ops.push_back(m + 1);
+    for (int m = 0; m < M; ++m) ops.push_back(-(m + 1));
+  } else if (order == STAGE_ORDER_EARLY_BACKWARD) {
+    int Kp = K < M ? K : M;
+    for (int m = 0; m < Kp; ++m) ops.push_back(m + 1);          // warm-up: inject K' micro-batches
+    for (int j = 0; j + Kp < M; ++j) {                          // steady: B_j frees what F_{j+K'} reuses
+      ops.push_back(-(j + 1));
+      ops.push_back(j + Kp + 1);
+    }
+    for (int m = M - Kp; m < M; ++m) ops.push_back(-(m + 1));   // drain
+  } else {
+    return fail(STAGE_E_BAD_ORDER, "unknown order %d", order);
+  }
+  return STAGE_OK;
+}
+
+// each micro-batch forward once then backward once, at most `limit` resident
+static int validate_ops(const int32_t* ops, int n, int M, int limit) {
+  if (n != 2 * M) return fail(STAGE_E_BAD_ORDER, "task list has %d entries, expected %d", n, 2 * M);
+  std::vector<int> state(M, 0);
+  int live = 0;
+  for (int i = 0; i < n; ++i) {
+    int m = (ops[i] > 0 ? ops[i] : -ops[i]) - 1;
+    if (ops[i] == 0 || m >= M) return fail(STAGE_E_BAD_ORDER, "task %d names micro-batch %d outside [0,%d)", i, m, M);
+    if (ops[i] > 0) {
+      if (state[m] != 0) return fail(STAGE_E_BAD_ORDER, "task %d: F%d twice", i, m);
+      if (live >= limit) return fail(STAGE_E_BAD_ORDER, "task %d: F%d would make %d micro-batches resident (limit %d)", i, m, live + 1, limit);
+      state[m] = 1; ++live;
+    } else {
+      if (state[m] != 1) return fail(STAGE_E_BAD_ORDER, "task %d: B%d without a live F%d", i, m, m);
+      state[m] = 2; --live;
+    }
+  }
+  return STAGE_OK;
+}
+
+// ------------------------------------------------------------------ C ABI
+extern "C" {
+
+const char* stage_last_error(void) { return g_err.c_str(); }
+
+int stage_query_sizes(const stage_config* cfg, stage_sizes* out) {
+  if (!cfg || !out) return fail(STAGE_E_NULL, "cfg and out must not be NULL");
+  TRY(check_config(*cfg));
+  Layout L;
+  build_layout(*cfg, L);
+  out->n_params = L.n_params;
+  out->weight_bytes = L.n_params * (cfg->dtype == STAGE_DTYPE_BF16 ? 2 : 4);
+  out->grad_bytes = L.grad_bytes;
+  out->slot_bytes = L.slot_bytes;
+  out->workspace_bytes = L.workspace_bytes;
+  out->arena_bytes = L.arena_bytes;
+  return STAGE_OK;
+}
+
+int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_dev, void* arena_dev,
+               size_t arena_bytes, void* hip_stream) {
+  if (!out || !cfg) return fail(STAGE_E_NULL, "out and cfg must not be NULL");
+  TRY(check_config(*cfg));
+  if (cfg->has_embedding || cfg->has_mlm_head)
+    return fail(STAGE_E_CONFIG, "embedding block and MLM head are not available in this build");
+  const bool dry = (cfg->flags & STAGE_FLAG_DRY_RUN) != 0;
+  if (!dry && (!weights_dev || !arena_dev)) return fail(STAGE_E_NULL, "weights_dev and arena_dev must not be NULL");
+  dapple_stage* h = new (std::nothrow) dapple_stage();
+  if (!h) return fail(STAGE_E_DEVICE, "out of host memory");
+  h->cfg = *cfg;
+  build_layout(*cfg, h->L);
+  if (!dry) {
+    if (arena_bytes < h->L.arena_bytes) {
+      size_t need = h->L.arena_bytes;
+      delete h;
+      return fail(STAGE_E_ARENA_SMALL, "arena has %zu bytes, %zu needed", arena_bytes, need);
+    }
+    if (((uintptr_t)arena_dev & 255) || ((uintptr_t)weights_dev & 15)) {
+      delete h;
+      return fail(STAGE_E_CONFIG, "arena_dev must be 256-byte aligned and weights_dev 16-byte aligned");
+    }
+  }
+  h->dt = cfg->dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32;
+  h->dry = dry;
+  h->W = (const char*)weights_dev;
+  h->arena = (char*)arena_dev;
+  h->grads = (float*)arena_dev;
+  h->st = (hipStream_t)hip_stream;
+  h->slot_of_mb.assign(cfg->max_slots, -1);
+  int rc = h->run(KC_COPY, 0, [&] { return launch_zero(h->grads, h->L.grad_bytes, h->st); });
+  if (rc != STAGE_OK) { delete h; return rc; }
+  *out = h;
+  return STAGE_OK;
+}
+
+int stage_destroy(stage_handle h) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  if (!h->dry) (void)hipStreamSynchronize(h->st);
+  for (auto& e : h->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  delete h;
+  return STAGE_OK;
+}
+
+static int find_slot(stage_handle h, int mb) {
+  for (size_t i = 0; i < h->slot_of_mb.size(); ++i)
+    if (h->slot_of_mb[i] == mb) return (int)i;
+  return -1;
+}
+
+int stage_fwd(stage_handle h, int mb, const void* x_dev, void* y_dev, const void* aux_dev) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  if (mb < 0) return fail(STAGE_E_BAD_ORDER, "micro-batch index %d is negative", mb);
+  if (!h->dry && (!x_dev || !y_dev)) return fail(STAGE_E_NULL, "x_dev and y_dev must not be NULL");
+  if (!h->dry && h->cfg.has_mlm_head && !aux_dev) return fail(STAGE_E_NULL, "aux_dev (targets) must not be NULL");
+  if (find_slot(h, mb) >= 0) return fail(STAGE_E_DUP_MB, "micro-batch %d is already resident", mb);
+  int s = find_slot(h, -1);
+  if (s < 0) return fail(STAGE_E_NO_SLOT, "all %d activation slots are in use", h->cfg.max_slots);
+  TRY(h->forward(s, x_dev, y_dev, aux_dev));
+  h->slot_of_mb[s] = mb;
+  ++h->live;
+  if (h->live > h->peak_live) h->peak_live = h->live;
+  ++h->fwd_tasks;
+  return STAGE_OK;
+}
+
+int stage_bwd(stage_handle h, int mb, const void* dy_dev, void* dx_dev) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  if (!h->dry && !h->cfg.has_mlm_head && !dy_dev) return fail(STAGE_E_NULL, "dy_dev must not be NULL");
+  if (!h->dry && !h->cfg.has_embedding && !dx_dev) return fail(STAGE_E_NULL, "dx_dev must not be NULL");
+  int s = mb < 0 ? -1 : find_slot(h, mb);
+  if (s < 0) return fail(STAGE_E_NOT_RESIDENT, "micro-batch %d has no live forward", mb);
+  TRY(h->backward(s, dy_dev, dx_dev));
+  h->slot_of_mb[s] = -1;   // released after its backward: the next injected micro-batch reuses it
+  --h->live;
+  ++h->bwd_tasks;
+  return STAGE_OK;
+}
+
+int stage_schedule_ops(int M, int K, int order, int32_t* ops_out, int capacity) {
+  if (!ops_out) return fail(STAGE_E_NULL, "ops_out must not be NULL");
+  std::vector<int32_t> ops;
+  TRY(make_schedule(M, K, order, ops));
+  if ((int)ops.size() > capacity) return fail(STAGE_E_BAD_ORDER, "capacity %d too small for %zu tasks", capacity, ops.size());
+  memcpy(ops_out, ops.data(), ops.size() * sizeof(int32_t));
+  return (int)ops.size();
+}
+
+int stage_run_schedule(stage_handle h, int M, int K, int order, const void* const* xs, const void* const* dys,
+                       void* const* ys, void* const* dxs, const void* const* auxs, const int32_t* explicit_ops,
+                       int n_ops) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  if (M < 1 || K < 1) return fail(STAGE_E_BAD_ORDER, "M and K must be positive (M=%d, K=%d)", M, K);
+  std::vector<int32_t> ops;
+  int limit;
+  if (order == STAGE_ORDER_EXPLICIT) {
+    if (!explicit_ops) return fail(STAGE_E_NULL, "explicit_ops must not be NULL");
+    ops.assign(explicit_ops, explicit_ops + (n_ops > 0 ? n_ops : 0));
+    limit = K;
+  } else {
+    TRY(make_schedule(M, K, order, ops));
+    limit = order == STAGE_ORDER_GPIPE ? M : (K < M ? K : M);
+  }
+  if (limit > h->cfg.max_slots)
+    return fail(STAGE_E_BAD_ORDER, "this order keeps %d micro-batches resident, the stage has %d slots", limit, h->cfg.max_slots);
+  TRY(validate_ops(ops.data(), (int)ops.size(), M, limit));
+  if (h->live != 0) return fail(STAGE_E_BAD_ORDER, "%d micro-batches are still resident from earlier calls", h->live);
+  if (!h->dry) {
+    const bool need_dy = !h->cfg.has_mlm_head, need_dx = !h->cfg.has_embedding, need_aux = h->cfg.has_mlm_head;
+    if (!xs || !ys || (need_dy && !dys) || (need_dx && !dxs) || (need_aux && !auxs))
+      return fail(STAGE_E_NULL, "a required pointer array is NULL");
+    for (int m = 0; m < M; ++m)
+      if (!xs[m] || !ys[m] || (need_dy && !dys[m]) || (need_dx && !dxs[m]) || (need_aux && !auxs[m]))
+        return fail(STAGE_E_NULL, "a device pointer of micro-batch %d is NULL", m);
+  }
+  for (int32_t op : ops) {
+    int m = (op > 0 ? op : -op) - 1;
+    if (op > 0) TRY(stage_fwd(h, m, xs ? xs[m] : nullptr, ys ? ys[m] : nullptr, auxs ? auxs[m] : nullptr));
+    else TRY(stage_bwd(h, m, dys ? dys[m] : nullptr, dxs ? dxs[m] : nullptr));
+  }
+  return STAGE_OK;
+}
+
+int stage_grads(stage_handle h, void** grads_dev, uint64_t* n) {
+  if (!h || !grads_dev || !n) return fail(STAGE_E_NULL, "handle, grads_dev and n must not be NULL");
+  *grads_dev = h->grads;
+  *n = h->L.n_params;
+  return STAGE_OK;
+}
+
+int stage_zero_grads(stage_handle h) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  return h->run(KC_COPY, 0, [&] { return launch_zero(h->grads, h->L.grad_bytes, h->st); });
+}
+
+int stage_stats(stage_handle h, stage_stats_t* out) {
+  if (!h || !out) return fail(STAGE_E_NULL, "handle and out must not be NULL");
+  out->slot_bytes = h->L.slot_bytes;
+  out->peak_activation_bytes = (uint64_t)h->peak_live * h->L.slot_bytes;
+  out->live_slots = h->live;
+  out->peak_live_slots = h->peak_live;
+  out->fwd_tasks = h->fwd_tasks;
+  out->bwd_tasks = h->bwd_tasks;
+  out->kernel_launches = h->launches;
+  return STAGE_OK;
+}
+
+int stage_reset_stats(stage_handle h) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  h->peak_live = h->live;
+  h->fwd_tasks = h->bwd_tasks = h->launches = 0;
+  return STAGE_OK;
+}
+
+int stage_profile_enable(stage_handle h, int on) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  if (!h->dry && hipStreamSynchronize(h->st) != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed");
+  h->profiling = on != 0;
+  h->events_used = 0;
+  return STAGE_OK;
+}
+
+int stage_profile_read(stage_handle h, int n, uint64_t* launches, double* ms, double* flops) {
+  if (!h || !launches || !ms || !flops) return fail(STAGE_E_NULL, "arguments must not be NULL");
+  if (!h->dry && hipStreamSynchronize(h->st) != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed");
+  for (int i = 0; i < n; ++i) { launches[i] = 0; ms[i] = 0; flops[i] = 0; }
+  for (size_t i = 0; i < h->events_used; ++i) {
+    const ProfEvent& e = h->events[i];
+    if (e.cls >= n) continue;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, e.a, e.b) != hipSuccess) return fail(STAGE_E_DEVICE, "hipEventElapsedTime failed");
+    launches[e.cls] += 1; ms[e.cls] += t; flops[e.cls] += e.flops;
+  }
+  h->events_used = 0;
+  return STAGE_OK;
+}
+
+const char* stage_profile_class_name(int i) { return (i >= 0 && i < KC_COUNT) ? kClassNames[i] : nullptr; }
+
+int stage_sync(stage_handle h) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  if (h->dry) return STAGE_OK;
+  hipError_t e = hipStreamSynchronize(h->st);
+  if (e != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed: %s", hipGetErrorString(e));
+  return STAGE_OK;
+}
+
+}  // extern "C"

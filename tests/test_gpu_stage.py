@@ -1,0 +1,117 @@
+"""GPU parity of the whole stage against the oracle, through the C ABI: every
+y_m, dx_m and every parameter-gradient tensor, both schedule orders, bit-identity
+across orders, and peak activation memory bounded by K."""
+import numpy as np
+import pytest
+
+from oracle import stage_oracle as O
+from paper_2007_01045_amd import binding as B
+from paper_2007_01045_amd import inputs as I
+from tests.stage_util import compare, make_inputs, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+# spec tolerances: relative L2 per tensor
+TOL_F32, TOL_BF16 = 1e-4, 2e-2
+SEED = I.DEFAULT_SEED
+
+
+def check_config(cfg, M, K, tol):
+    theta, mbs = make_inputs(cfg, SEED, M)
+    st, ref = run_oracle(cfg, theta, mbs, M, K)
+    eb = run_gpu(cfg, theta, mbs, M, K, B.ORDER_EARLY_BACKWARD)
+    gp = run_gpu(cfg, theta, mbs, M, K, B.ORDER_GPIPE)
+    worst = compare(cfg, st, ref, eb, tol, M)
+    compare(cfg, st, ref, gp, tol, M)
+    # the two orders run the same kernels on the same data and add the micro-batch
+    # gradients in the same sequence: results must agree bit for bit
+    assert np.array_equal(eb["grads"], gp["grads"])
+    for m in range(M):
+        assert np.array_equal(eb["ys"][m], gp["ys"][m])
+        if eb["dxs"] is not None:
+            assert np.array_equal(eb["dxs"][m], gp["dxs"][m])
+    # peak activation memory: K slots against M slots
+    assert eb["stats"]["peak_live"] == min(K, M) and gp["stats"]["peak_live"] == M
+    assert eb["stats"]["peak_bytes"] == min(K, M) * eb["stats"]["slot_bytes"]
+    assert gp["stats"]["peak_bytes"] == M * gp["stats"]["slot_bytes"]
+    assert ref["peak_live"] == min(K, M)
+    return worst
+
+
+def test_tiny_fp32_config():
+    cfg = I.CONFIGS["tiny"]
+    worst = check_config(cfg, cfg.M, cfg.K, TOL_F32)
+    print("tiny fp32 worst:", worst)
+
+
+def test_fp32_ragged_shapes():
+    # sizes that are not multiples of the kernels' tiles: plain kernels, several blocks
+    cfg = I.StageConfig(2, 72, 6, 100, 19, 3, 3, 2, "f32", ln_eps=1e-5)
+    check_config(cfg, 3, 2, TOL_F32)
+
+
+def test_bf16_mfma_path_small():
+    # d = 64, s multiple of 64: MFMA GEMMs and MFMA attention; T = 384 gives ragged tiles
+    cfg = I.StageConfig(2, 256, 4, 512, 192, 2, 5, 2, "bf16")
+    worst = check_config(cfg, 5, 2, TOL_BF16)
+    print("bf16 small worst:", worst)
+
+
+def test_bf16_plain_fallback_shapes():
+    # head dim 32 and odd sequence: plain attention kernels, MFMA GEMMs where they apply
+    cfg = I.StageConfig(1, 64, 2, 128, 24, 2, 2, 1, "bf16")
+    check_config(cfg, 2, 1, TOL_BF16)
+
+
+def test_K_equal_one_and_K_above_M():
+    cfg = I.CONFIGS["tiny"]
+    theta, mbs = make_inputs(cfg, SEED, 3)
+    st, ref = run_oracle(cfg, theta, mbs, 3, 1)
+    a = run_gpu(cfg, theta, mbs, 3, 1, B.ORDER_EARLY_BACKWARD)
+    b = run_gpu(cfg, theta, mbs, 3, 7, B.ORDER_EARLY_BACKWARD, max_slots=7)
+    compare(cfg, st, ref, a, TOL_F32, 3)
+    assert a["stats"]["peak_live"] == 1 and b["stats"]["peak_live"] == 3
+    assert np.array_equal(a["grads"], b["grads"])
+
+
+def test_explicit_order_descending_backwards_within_tolerance():
+    cfg = I.CONFIGS["tiny"]
+    theta, mbs = make_inputs(cfg, SEED, 4)
+    st, ref = run_oracle(cfg, theta, mbs, 4, 4)
+    ops = [("F", m) for m in range(4)] + [("B", m) for m in reversed(range(4))]
+    g = run_gpu(cfg, theta, mbs, 4, 4, B.ORDER_EXPLICIT, max_slots=4, explicit_ops=ops)
+    compare(cfg, st, ref, g, TOL_F32, 4)
+
+
+def test_repeat_runs_are_bit_identical_and_zero_grads_works():
+    cfg = I.StageConfig(2, 256, 4, 512, 128, 2, 3, 2, "bf16")
+    theta, mbs = make_inputs(cfg, SEED, 3)
+    a = run_gpu(cfg, theta, mbs, 3, 2, B.ORDER_EARLY_BACKWARD)
+    b = run_gpu(cfg, theta, mbs, 3, 2, B.ORDER_EARLY_BACKWARD)
+    assert np.array_equal(a["grads"], b["grads"])
+    # two iterations without zeroing accumulate; with zeroing they do not
+    r = B.StageRunner(__import__("tests.stage_util", fromlist=["c_config"]).c_config(cfg, 2), theta)
+    try:
+        T, H = cfg.tokens, cfg.hidden
+        xs = [r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+        dys = [r.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
+        r.run(3, 2, B.ORDER_EARLY_BACKWARD, xs, dys)
+        r.run(3, 2, B.ORDER_EARLY_BACKWARD, xs, dys)
+        torch.cuda.synchronize()
+        twice = r.grads.cpu().numpy().astype(np.float64)
+        assert np.linalg.norm(twice - 2 * a["grads"]) <= 1e-5 * np.linalg.norm(twice)
+        B.stage_zero_grads(r.h)
+        r.run(3, 2, B.ORDER_EARLY_BACKWARD, xs, dys)
+        torch.cuda.synchronize()
+        assert np.array_equal(r.grads.cpu().numpy(), a["grads"])
+    finally:
+        r.close()
+
+
+def test_bert_large_shaped_stage_full_size():
+    """The benchmark's configuration at full size: 6 layers, H 1024, 16 heads, FFN 4096,
+    seq 512, micro-batch 4, M 8, K 4 (the oracle needs about a minute of CPU)."""
+    cfg = I.CONFIGS["bert_large"]
+    worst = check_config(cfg, cfg.M, cfg.K, TOL_BF16)
+    print("bert_large worst:", worst)
