@@ -1,0 +1,172 @@
+"""Benchmark of the stage hot path on one MI355X.
+
+A step = stage_zero_grads + stage_run_schedule(M, K, early-backward) over one batch
+of synthetic micro-batches already resident in HBM, + stream sync.  Workload: the
+BERT-Large-shaped stage (6 layers, hidden 1024, 16 heads, FFN 4096, seq 512,
+micro-batch 4, M = 8, K = 4, bf16 storage with fp32 accumulation).
+
+Prints one JSON line: stage samples/s (value), algorithmic TFLOP/s and its fraction
+of the bf16 MFMA peak, peak activation bytes for K-slot early-backward against
+M-slot GPipe order, the roofline of the dominant kernel (the MFMA GEMM, timed with
+HIP events on the stage's stream in a separate profiled pass over the same steps)
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+
+
+def stage_flops(cfg, M):
+    """Algorithmic flops of one iteration: per layer and micro-batch the forward is
+    24 T H^2 (four linear layers at F = 4H; in general 8 T H^2 + 4 T H F) + 4 T s H
+    (QK^T and PV); the backward is twice that."""
+    T, H, F, s = cfg.tokens, cfg.hidden, cfg.ffn, cfg.seq
+    fwd = 8.0 * T * H * H + 4.0 * T * H * F + 4.0 * T * s * H
+    return 3.0 * fwd * cfg.n_layers * M
+
+
+def cpu_baseline(cfg, seed, M_sample, K_sample):
+    import numpy as np
+    from oracle import stage_oracle as O
+    from paper_2007_01045_amd import inputs as I
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    theta = I.make_params(cfg, seed).astype(np.float64)
+    st = O.Stage(I.param_layout(cfg), theta, cfg.n_layers, cfg.n_heads, cfg.ln_eps)
+    mbs = [I.make_microbatch(cfg, seed, m) for m in range(M_sample)]
+    xs = [mb["x"].astype(np.float64) for mb in mbs]
+    dys = [mb["dy"].astype(np.float64) for mb in mbs]
+    t0 = time.perf_counter()
+    O.run_schedule(st, M_sample, K_sample, O.EARLY_BACKWARD, xs, dys)
+    dt = time.perf_counter() - t0
+    return {"value": M_sample * cfg.micro_batch / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{M_sample} of the {cfg.M} micro-batches (K={K_sample}) of the same stage, float64 numpy, "
+                      f"{dt:.1f} s", "tflops": stage_flops(cfg, M_sample) / dt / 1e12}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="bert_large")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2007_01045_amd import binding as B
+    from paper_2007_01045_amd import inputs as I
+    from tests.stage_util import c_config
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    B.load()           # raises if the HIP library has not been built: there is no fallback
+    cfg = I.CONFIGS[args.workload]
+    seed = I.DEFAULT_SEED if args.seed is None else args.seed
+    M, K, T, H = cfg.M, cfg.K, cfg.tokens, cfg.hidden
+    theta = I.make_params(cfg, seed)
+    mbs = [I.make_microbatch(cfg, seed, m) for m in range(M)]
+
+    results = {}
+    peak_bytes = {}
+    runner = None
+    for order_name, order, slots in (("gpipe", B.ORDER_GPIPE, M), ("early_backward", B.ORDER_EARLY_BACKWARD, K)):
+        r = B.StageRunner(c_config(cfg, slots), theta)
+        xs = [r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+        dys = [r.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
+        ys = [r.empty_act() for _ in range(M)]
+        dxs = [r.empty_act() for _ in range(M)]
+        ptr = lambda ts: [t.data_ptr() for t in ts]
+        px, pdy, py, pdx = ptr(xs), ptr(dys), ptr(ys), ptr(dxs)
+
+        def step():
+            B.stage_zero_grads(r.h)
+            B.stage_run_schedule(r.h, M, K, order, px, pdy, py, pdx)
+
+        for _ in range(args.warmup):
+            step()
+        B.stage_sync(r.h)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        B.stage_sync(r.h)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        results[order_name] = dt / args.steps
+        st = B.stage_stats(r.h)
+        peak_bytes[order_name] = int(st.peak_activation_bytes)
+        if order_name == "early_backward":
+            runner = (r, step)
+        else:
+            del xs, dys, ys, dxs
+            r.close()
+            del r
+            torch.cuda.empty_cache()
+
+    # per-kernel-class times: the same steps again with HIP events around every launch
+    r, step = runner
+    B.stage_profile_enable(r.h, True)
+    prof_steps = min(args.steps, 5)
+    for _ in range(prof_steps):
+        step()
+    prof = B.stage_profile_read(r.h)
+    B.stage_profile_enable(r.h, False)
+    gemm = [prof[k] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")]
+    g_ms = sum(p["ms"] for p in gemm)
+    g_fl = sum(p["flops"] for p in gemm)
+    g_n = sum(p["launches"] for p in gemm)
+    achieved = g_fl / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
+    classes = {k: {"launches_per_step": v["launches"] / prof_steps, "ms_per_step": v["ms"] / prof_steps,
+                   "tflops": (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["ms"] > 0 and v["flops"] > 0 else None}
+               for k, v in prof.items() if v["launches"]}
+    r.close()
+
+    sec = results["early_backward"]
+    flops = stage_flops(cfg, M)
+    out = {
+        "metric": "stage samples/sec + MFMA util (%) + peak activation bytes vs GPipe order",
+        "value": M * cfg.micro_batch / sec, "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: L={cfg.n_layers} H={cfg.hidden} A={cfg.n_heads} F={cfg.ffn} "
+                               f"s={cfg.seq} b={cfg.micro_batch} M={M} K={K}, early-backward order",
+                   "seed": seed},
+        "tflops_algorithmic": flops / sec / 1e12,
+        "mfma_peak_frac_algorithmic": flops / sec / 1e12 / PEAK_BF16_TFLOPS,
+        "gpipe_order": {"samples_per_s": M * cfg.micro_batch / results["gpipe"], "ms_per_step": results["gpipe"] * 1e3},
+        "peak_activation_bytes": {"early_backward_K_slots": peak_bytes["early_backward"],
+                                  "gpipe_M_slots": peak_bytes["gpipe"],
+                                  "ratio": peak_bytes["early_backward"] / peak_bytes["gpipe"]},
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel (all linear-layer products: fwd, dgrad, wgrad)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches_per_step": g_n / prof_steps, "avg_launch_us": g_ms * 1e3 / max(g_n, 1)},
+        "kernel_classes": classes,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, seed, 2, 2)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -4,16 +4,19 @@
 //
 //  * gemm_mfma_kernel: bf16 operands, fp32 accumulation on the gfx950 matrix
 //    cores (v_mfma_f32_32x32x16_bf16).  256 threads = 4 waves in a 2x2 grid over a
-//    BM x BN tile, BK = 64 per step, LDS double-buffered.  k-contiguous operands
-//    sit in LDS as [row][64] with an XOR swizzle of the 16-byte chunks and are
-//    read with 128-bit loads; k-strided operands sit as [k][rows+16] and are read
-//    with the LDS transpose read, so no transposed copy of an activation or a
-//    weight is ever made in HBM.  The MFMA is issued with the B fragment as its
+//    BM x BN tile, BK = 64 per step, LDS double-buffered and filled by buffer loads
+//    that write straight into LDS.  k-contiguous operands sit in LDS as [row][64]
+//    and are read with 128-bit loads; k-strided operands sit as [k][rows] and are
+//    read with the LDS transpose read, so no transposed copy of an activation or a
+//    weight is ever made in HBM (both layouts XOR-swizzled against bank conflicts).  The MFMA is issued with the B fragment as its
 //    first operand: each lane then owns 4 consecutive output columns of one
 //    output row, which the epilogue stages through LDS into coalesced stores.
 //  * gemm_plain_kernel: one thread per output element, fp32 accumulation in k
 //    order; used for fp32 stages (the tiny configuration) and for shapes the MFMA
 //    kernel does not take.
+#include <cstdlib>
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
@@ -43,8 +46,12 @@ __global__ void gemm_plain_kernel(GemmArgs g) {
   int row = blockIdx.y * blockDim.y + threadIdx.y;
   int z = blockIdx.z;
   if (row >= g.M || col >= g.N) return;
-  const T* A = (const T*)g.A + z * g.sA;
-  const T* B = (const T*)g.B + z * g.sB;
+  const T* A = g.Az[0] ? (const T*)g.Az[z] : (const T*)g.A + z * g.sA;
+  const T* B = g.Bz[0] ? (const T*)g.Bz[z] : (const T*)g.B + z * g.sB;
+  if (g.Cz[0]) {
+    g.C = g.Cz[z];
+    g.sC = 0;
+  }
   float acc = 0.f;
   int nseg = g.K / g.kseg_len;
   for (int s = 0; s < nseg; ++s) {
@@ -62,98 +69,152 @@ __global__ void gemm_plain_kernel(GemmArgs g) {
 
 // ------------------------------------------------------------------ MFMA kernel
 constexpr int BK = 64;
-constexpr int TPAD = 16;  // row padding (elements) of a k-strided LDS tile
+constexpr unsigned BUF_RSRC_FLAGS = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
 
-template <int R, bool KS>
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// One operand's [R x 64] tile of a k-step in LDS, filled by buffer loads that
+// write straight into LDS (16 bytes per lane, 1 KiB contiguous per wave
+// instruction; out-of-range offsets read as zero, so ragged edges need no
+// branches) and read back as MFMA fragments.
+//   k-contiguous operand: LDS [row][8 chunks of 16 B], chunk' = chunk ^ ((row >> 1) & 7)
+//   k-strided operand:    LDS [k][R/8 chunks],         chunk' = chunk ^ kswz(k)
+// LDS has 64 banks of 4 bytes: a 128-bit read is served 16 lanes at a time and a
+// 64-bit (transpose) read 32 lanes at a time, each group needing 256 distinct
+// bytes modulo 256.  The swizzles give exactly that (measured: 5 and 2.6 clocks
+// per wave instruction against 8 and 8 unswizzled); they are applied on the global
+// side (which chunk a lane fetches), since the LDS side of a direct load is fixed
+// to lane order.
+template <int R, bool KS, int NW>
 struct OperandTile {
-  static constexpr int NCH = R * 8 / 256;                   // 16-byte chunks per thread per k-tile
-  static constexpr int LDS_ELEMS = KS ? BK * (R + TPAD) : R * BK;
-  uint4 regs[NCH];
+  static constexpr int NI = R * 8 / (64 * NW);  // load instructions per wave per k-step
+  static constexpr int LDS_ELEMS = R * BK;
+    static_assert(R * 8 % (64 * NW) == 0, "tile rows must split evenly over the waves");
+  int voff[NI];  // per-lane byte offset of each load inside the k-step's slab
 
-  // base: operand pointer already offset for batch and k-segment; r0: first row of the
-  // tile; k0: first k inside the segment
-  __device__ __forceinline__ void load(const bf16* base, int ld, int r0, int k0, int rmax, int kvalid, int tid) {
+  // chunk swizzle of k row k of a k-strided tile: rows of 256 B or more rotate by 64 B per
+  // row (4 rows cover 256 B); rows of 128 B alternate halves every second row
+  static __device__ __forceinline__ int kswz(int k) { return R >= 128 ? (k & 3) << 2 : ((k >> 1) & 1) << 2; }
+
+  __device__ __forceinline__ void init(int ld, int r0, int wave, int lane) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int c = tid + 256 * i;
-      const bf16* p;
-      bool ok;
+    for (int j = 0; j < NI; ++j) {
+      int pos = (j * NW + wave) * 64 + lane;
       if (!KS) {
-        int row = c >> 3, kc = c & 7;
-        ok = (r0 + row) < rmax;
-        p = base + (long)(r0 + row) * ld + k0 + kc * 8;
+        int row = pos >> 3, kc = (pos & 7) ^ ((row >> 1) & 7);
+        voff[j] = ((r0 + row) * ld + kc * 8) * 2;
       } else {
-        int krow = c / (R / 8), rc = c % (R / 8);
-        ok = (k0 + krow) < kvalid && (r0 + rc * 8) < rmax;
-        p = base + (long)(k0 + krow) * ld + r0 + rc * 8;
+        int krow = pos / (R / 8), c = (pos % (R / 8)) ^ kswz(krow);
+        voff[j] = (krow * ld + r0 + c * 8) * 2;
       }
-      regs[i] = ok ? *(const uint4*)p : make_uint4(0, 0, 0, 0);
     }
   }
-  __device__ __forceinline__ void store(bf16* S, int tid) const {
+  // base: first element of this k-step's slab (k-contiguous: operand + k0; k-strided:
+  // operand + k0*ld); avail: bytes from base to the end of the valid operand region
+  __device__ __forceinline__ void load(const bf16* base, long avail, bf16* S, int wave) const {
+    unsigned rec = avail <= 0 ? 0u : (avail > 0x7fffffffL ? 0x7fffffffu : (unsigned)avail);
+    __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, rec, BUF_RSRC_FLAGS);
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int c = tid + 256 * i;
-      if (!KS) {
-        int row = c >> 3, kc = c & 7;
-        *(uint4*)(S + row * BK + ((kc ^ (row & 7)) << 3)) = regs[i];
-      } else {
-        int krow = c / (R / 8), rc = c % (R / 8);
-        *(uint4*)(S + krow * (R + TPAD) + rc * 8) = regs[i];
-      }
-    }
+    for (int j = 0; j < NI; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(S + (j * NW + wave) * 512), 16, voff[j], 0, 0, 0);
   }
   // MFMA fragment for rows r0..r0+31 (lane & 31), k = kk*16 + 8*(lane>>5) + 0..7
   static __device__ __forceinline__ bf16x8 frag(const bf16* S, int r0, int kk, int lane) {
     if (!KS) {
       int row = r0 + (lane & 31);
       int kc = kk * 2 + (lane >> 5);
-      return *(const bf16x8*)(S + row * BK + ((kc ^ (row & 7)) << 3));
+      return *(const bf16x8*)(S + row * BK + ((kc ^ ((row >> 1) & 7)) << 3));
     } else {
       int i16 = lane & 15, g16 = (lane >> 4) & 1, h = lane >> 5;
       int krow = kk * 16 + 8 * h + (i16 >> 2);
       int col = r0 + 16 * g16 + 4 * (i16 & 3);
-      const bf16* p = S + krow * (R + TPAD) + col;
-      return join8(lds_read_tr16(p), lds_read_tr16(p + 4 * (R + TPAD)));
+      int sw = kswz(i16 >> 2);  // depends on krow & 3 only: the same for krow + 4
+      const bf16* p = S + krow * R + (((col >> 3) ^ sw) << 3) + (col & 7);
+      return join8(lds_read_tr16(p), lds_read_tr16(p + 4 * R));
     }
   }
 };
 
-template <int BM, int BN, bool AKS, bool BKS>
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
 struct GemmTile {
-  static constexpr int WM = BM / 2, WN = BN / 2, MI = WM / 32, NI = WN / 32;
-  typedef OperandTile<BM, AKS> TA;
-  typedef OperandTile<BN, BKS> TB;
+  static constexpr int NW = WGM * WGN, NT = 64 * NW;
+  static constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
+  typedef OperandTile<BM, AKS, NW> TA;
+  typedef OperandTile<BN, BKS, NW> TB;
   static constexpr int STAGE_ELEMS = TA::LDS_ELEMS + TB::LDS_ELEMS;
   static constexpr int EPI_LD = WN + 4;  // fp32 staging row
   static constexpr size_t MAIN_BYTES = 2 * (size_t)STAGE_ELEMS * sizeof(bf16);
-  static constexpr size_t EPI_BYTES = 4 * (size_t)32 * EPI_LD * sizeof(float);
+  static constexpr size_t EPI_BYTES = (size_t)NW * 32 * EPI_LD * sizeof(float);
   static constexpr size_t LDS_BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
 };
 
-template <int BM, int BN, bool AKS, bool BKS>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
-  typedef GemmTile<BM, BN, AKS, BKS> CFG;
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  typedef GemmTile<BM, BN, WGM, WGN, AKS, BKS> CFG;
   typedef typename CFG::TA TA;
   typedef typename CFG::TB TB;
   constexpr int MI = CFG::MI, NI = CFG::NI;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   bf16* lds = (bf16*)smem;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm0 = (wave >> 1) * CFG::WM, wn0 = (wave & 1) * CFG::WN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave / WGN) * CFG::WM, wn0 = (wave % WGN) * CFG::WN;
 
-  // tile index: consecutive workgroups land on different XCDs (round-robin over 8),
-  // so give each XCD a contiguous run of tiles that share operand panels in its L2
-  int bid = blockIdx.x;
-  const int ntiles = tiles_m * tiles_n;
-  if ((ntiles & 7) == 0) bid = (bid & 7) * (ntiles >> 3) + (bid >> 3);
-  const int tm = bid / tiles_n, tn = bid % tiles_n;
+  // Tile index.  Consecutive workgroups land on different XCDs (round-robin over 8), and
+  // each XCD has its own L2.  Cut the tile grid into pm x pn = 8 rectangles, one per XCD,
+  // so that the A and B panels an XCD touches are as few as possible and are reused by
+  // all its tiles out of its L2; inside a rectangle walk column-blocks of 4 tiles.
+  int tm, tn;
+  {
+    const int bid = blockIdx.x;
+    const int ntiles = tiles_m * tiles_n;
+    int pm = 0, best = 1 << 30;
+#pragma unroll
+    for (int c = 1; c <= 8; c <<= 1) {
+      int pn = 8 / c;
+      if (tiles_m % c == 0 && tiles_n % pn == 0) {
+        int cost = (tiles_m / c) * BM + (tiles_n / pn) * BN;
+        if (cost < best) { best = cost; pm = c; }
+      }
+    }
+    if (pm == 0 || (ntiles & 7)) {
+      tm = bid / tiles_n;
+      tn = bid % tiles_n;
+    } else {
+      const int pn = 8 / pm, rm = tiles_m / pm, rn = tiles_n / pn;
+      const int xcd = bid & 7, local = bid >> 3;
+      const int lm = local % rm, ln = local / rm;   // walk down a column of the rectangle first
+      tm = (xcd / pn) * rm + lm;
+      tn = (xcd % pn) * rn + ln;
+    }
+  }
   const int m0 = tm * BM, n0 = tn * BN;
   const int z = blockIdx.z;
 
-  const bf16* Ab = (const bf16*)g.A + z * g.sA;
-  const bf16* Bb = (const bf16*)g.B + z * g.sB;
+  const bf16* Ab = g.Az[0] ? (const bf16*)g.Az[z] : (const bf16*)g.A + z * g.sA;
+  const bf16* Bb = g.Bz[0] ? (const bf16*)g.Bz[z] : (const bf16*)g.B + z * g.sB;
+  void* const Cb = g.Cz[0] ? g.Cz[z] : g.C;
+  const int nk = g.K / BK;
+  const int tiles_per_seg = g.kseg_len / BK;
+  // bytes of one segment of each operand that may be read (beyond: zero)
+  const long a_ext = AKS ? ((long)(g.k_valid - 1) * g.lda + g.M) * 2 : ((long)(g.M - 1) * g.lda + g.kseg_len) * 2;
+  const long b_ext = BKS ? ((long)(g.k_valid - 1) * g.ldb + g.N) * 2 : ((long)(g.N - 1) * g.ldb + g.kseg_len) * 2;
+
+  TA ta;
+  TB tb;
+  ta.init(g.lda, m0, wave, lane);
+  tb.init(g.ldb, n0, wave, lane);
+
+  auto issue_loads = [&](int kt) {
+    int seg = kt / tiles_per_seg;
+    int k0 = (kt - seg * tiles_per_seg) * BK;
+    long aoff = AKS ? (long)k0 * g.lda : (long)k0;
+    long boff = BKS ? (long)k0 * g.ldb : (long)k0;
+    bf16* S = lds + (kt & 1) * CFG::STAGE_ELEMS;
+    ta.load(Ab + seg * g.segA + aoff, a_ext - aoff * 2, S, wave);
+    tb.load(Bb + seg * g.segB + boff, b_ext - boff * 2, S + TA::LDS_ELEMS, wave);
+  };
 
   f32x16 acc[MI][NI];
 #pragma unroll
@@ -163,55 +224,75 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g, int tiles_m,
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  TA ta;
-  TB tb;
-  const int nk = g.K / BK;
-  const int tiles_per_seg = g.kseg_len / BK;
-
-  auto issue_loads = [&](int kt) {
-    int seg = kt / tiles_per_seg;
-    int k0 = (kt - seg * tiles_per_seg) * BK;
-    ta.load(Ab + seg * g.segA, g.lda, m0, k0, g.M, g.k_valid, tid);
-    tb.load(Bb + seg * g.segB, g.ldb, n0, k0, g.N, g.k_valid, tid);
+  // Software pipeline.  Global->LDS: tile kt+2 is requested as soon as every wave has
+  // left tile kt's buffer, so a request has a whole tile of MFMA time to land.
+  // LDS->registers: the fragments of k-step kk+1 are requested before the MFMAs of
+  // k-step kk are issued (two fragment sets), so the matrix cores never wait for an
+  // LDS round trip except once per tile.
+  struct Frags {
+    bf16x8 a[MI], b[NI];
+  };
+  auto load_frags = [&](Frags& f, const bf16* As, int kk) {
+    const bf16* Bs = As + TA::LDS_ELEMS;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) f.a[i] = TA::frag(As, wm0 + i * 32, kk, lane);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) f.b[j] = TB::frag(Bs, wn0 + j * 32, kk, lane);
+  };
+  auto mfma_step = [&](const Frags& f) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
   };
 
   issue_loads(0);
-  ta.store(lds, tid);
-  tb.store(lds + TA::LDS_ELEMS, tid);
+  if (nk > 1) issue_loads(1);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
   __syncthreads();
+  Frags cur, nxt;
+  load_frags(cur, lds, 0);
 
   for (int kt = 0; kt < nk; ++kt) {
     const bf16* As = lds + (kt & 1) * CFG::STAGE_ELEMS;
-    const bf16* Bs = As + TA::LDS_ELEMS;
-    if (kt + 1 < nk) issue_loads(kt + 1);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 a[MI], b[NI];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) a[i] = TA::frag(As, wm0 + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < NI; ++j) b[j] = TB::frag(Bs, wn0 + j * 32, kk, lane);
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+    for (int kk = 0; kk < BK / 16 - 1; ++kk) {
+      load_frags(nxt, As, kk + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_step(cur);
+      __builtin_amdgcn_sched_barrier(0);
+      cur = nxt;
     }
-    if (kt + 1 < nk) {
-      bf16* An = lds + ((kt + 1) & 1) * CFG::STAGE_ELEMS;
-      ta.store(An, tid);
-      tb.store(An + TA::LDS_ELEMS, tid);
-    }
+    // cur holds the last k-step of this tile: the buffer is no longer needed
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
+    if (kt + 1 < nk) load_frags(nxt, lds + ((kt + 1) & 1) * CFG::STAGE_ELEMS, 0);
+    if (kt + 2 < nk) issue_loads(kt + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(cur);
+    __builtin_amdgcn_sched_barrier(0);
+    cur = nxt;
   }
+  __syncthreads();
 
   // epilogue: per wave, 32 output rows at a time through an fp32 LDS staging tile.
   // acc[i][j][v]: row = wm0 + 32 i + (lane & 31), col = wn0 + 32 j + 8 (v>>2) + 4 (lane>>5) + (v&3)
+  // epilogue: per wave, 32 output rows at a time through an fp32 LDS staging tile that
+  // turns "a lane owns 4 columns of one row" into row-contiguous stores.
+  // acc[i][j][v]: row = wm0 + 32 i + (lane & 31), col = wn0 + 32 j + 8 (v>>2) + 4 (lane>>5) + (v&3)
+  // All LDS reads (and aux / C reads) of a half block are issued before the first use,
+  // so their latencies overlap instead of adding up.
   float* stg = (float*)smem + wave * 32 * CFG::EPI_LD;
-  const long zc = z * g.sC, zbias = z * g.sBias;
-  constexpr int C4 = CFG::WN / 4;  // float4 per staged row
-#pragma unroll
-  for (int i = 0; i < MI; ++i) {
+  const long zc = g.Cz[0] ? 0 : z * g.sC, zbias = z * g.sBias;
+  constexpr int C4 = CFG::WN / 4;             // float4 per staged row
+  constexpr int NIT = 32 * C4 / 64;           // float4 per lane per 32-row block
+  constexpr int HB = NIT > 8 ? 8 : NIT;       // processed HB at a time
+  const int epi = g.epi;
+  // one 32-row block; the block index is a compile-time constant so that the
+  // accumulators are always addressed statically (they must stay in registers)
+  auto store_block = [&](auto I) {
+    constexpr int i = decltype(I)::value;
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -219,64 +300,114 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g, int tiles_m,
         float4 v4 = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
         *(float4*)(stg + (lane & 31) * CFG::EPI_LD + j * 32 + 8 * q + 4 * (lane >> 5)) = v4;
       }
-    __syncthreads();
-#pragma unroll 4
-    for (int it = 0; it < 32 * C4 / 64; ++it) {
-      int idx = it * 64 + lane;
-      int r = idx / C4, c4 = idx % C4;
-      int row = m0 + wm0 + i * 32 + r;
-      int col = n0 + wn0 + c4 * 4;
-      if (row < g.M && col < g.N) {
-        float4 t = *(const float4*)(stg + r * CFG::EPI_LD + c4 * 4);
-        if (col + 3 < g.N) {
-          float tv[4] = {t.x, t.y, t.z, t.w};
-          if (g.epi & EPI_BIAS) {
-            bf16x4 bv = *(const bf16x4*)((const bf16*)g.bias + zbias + col);
+    // the staging tile is private to the wave and a wave's LDS instructions execute in
+    // order: no workgroup barrier is needed (one would also wait for the stores below)
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int e = 0; e < 4; ++e) tv[e] += (float)bv[e];
-          }
-          if (g.epi & (EPI_ADD | EPI_MUL)) {
-            bf16x4 xv = *(const bf16x4*)((const bf16*)g.aux + zc + (long)row * g.ldaux + col);
+    for (int hb = 0; hb < NIT; hb += HB) {
+      float4 t[HB];
+      int rows[HB], cols[HB];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) tv[e] = (g.epi & EPI_ADD) ? tv[e] + (float)xv[e] : tv[e] * (float)xv[e];
-          }
-          long o = zc + (long)row * g.ldc + col;
-          if (g.epi & EPI_GELU) {
-            bf16x4 gv, gp;
+      for (int u = 0; u < HB; ++u) {
+        int idx = (hb + u) * 64 + lane;
+        int r = idx / C4, c4 = idx % C4;
+        rows[u] = m0 + wm0 + i * 32 + r;
+        cols[u] = n0 + wn0 + c4 * 4;
+        t[u] = *(const float4*)(stg + r * CFG::EPI_LD + c4 * 4);
+      }
+      {
+        if (epi & EPI_BIAS) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              gv[e] = (bf16)gelu_f(tv[e]);
-              gp[e] = (bf16)gelu_grad_f(tv[e]);
+          for (int u = 0; u < HB; ++u)
+            if (cols[u] < g.N) {
+              bf16x4 bv = *(const bf16x4*)((const bf16*)g.bias + zbias + cols[u]);
+              t[u].x += (float)bv[0]; t[u].y += (float)bv[1]; t[u].z += (float)bv[2]; t[u].w += (float)bv[3];
             }
-            *(bf16x4*)((bf16*)g.C + o) = gv;
-            *(bf16x4*)((bf16*)g.C2 + o) = gp;
-          } else if (g.epi & EPI_ACC32) {
-            float4* cp = (float4*)((float*)g.C + o);
-            float4 c = *cp;
-            c.x += tv[0]; c.y += tv[1]; c.z += tv[2]; c.w += tv[3];
-            *cp = c;
-          } else {
-            bf16x4 ov;
+        }
+        if (epi & (EPI_ADD | EPI_MUL)) {
+          bf16x4 xv[HB];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) ov[e] = (bf16)tv[e];
-            *(bf16x4*)((bf16*)g.C + o) = ov;
+          for (int u = 0; u < HB; ++u) {
+            bool ok = rows[u] < g.M && cols[u] < g.N;
+            long o = ok ? zc + (long)rows[u] * g.ldaux + cols[u] : zc;
+            xv[u] = *(const bf16x4*)((const bf16*)g.aux + o);
           }
+#pragma unroll
+          for (int u = 0; u < HB; ++u) {
+            if (epi & EPI_ADD) {
+              t[u].x += (float)xv[u][0]; t[u].y += (float)xv[u][1]; t[u].z += (float)xv[u][2]; t[u].w += (float)xv[u][3];
+            } else {
+              t[u].x *= (float)xv[u][0]; t[u].y *= (float)xv[u][1]; t[u].z *= (float)xv[u][2]; t[u].w *= (float)xv[u][3];
+            }
+          }
+        }
+        if (epi & EPI_ACC32) {
+          float4 cv[HB];
+#pragma unroll
+          for (int u = 0; u < HB; ++u) {
+            bool ok = rows[u] < g.M && cols[u] < g.N;
+            long o = ok ? zc + (long)rows[u] * g.ldc + cols[u] : zc;
+            cv[u] = *(const float4*)((const float*)Cb + o);
+          }
+#pragma unroll
+          for (int u = 0; u < HB; ++u)
+            if (rows[u] < g.M && cols[u] < g.N) {
+              cv[u].x += t[u].x; cv[u].y += t[u].y; cv[u].z += t[u].z; cv[u].w += t[u].w;
+              *(float4*)((float*)Cb + zc + (long)rows[u] * g.ldc + cols[u]) = cv[u];
+            }
+        } else if (epi & EPI_GELU) {
+#pragma unroll
+          for (int u = 0; u < HB; ++u)
+            if (rows[u] < g.M && cols[u] < g.N) {
+              float tv[4] = {t[u].x, t[u].y, t[u].z, t[u].w};
+              bf16x4 gv, gp;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                gv[e] = (bf16)gelu_f(tv[e]);
+                gp[e] = (bf16)gelu_grad_f(tv[e]);
+              }
+              long o = zc + (long)rows[u] * g.ldc + cols[u];
+              *(bf16x4*)((bf16*)Cb + o) = gv;
+              *(bf16x4*)((bf16*)g.C2 + o) = gp;
+            }
         } else {
-          float tv[4] = {t.x, t.y, t.z, t.w};
-          for (int e = 0; e < 4 && col + e < g.N; ++e) epilogue_store<bf16>(g, zc, zbias, row, col + e, tv[e]);
+#pragma unroll
+          for (int u = 0; u < HB; ++u)
+            if (rows[u] < g.M && cols[u] < g.N) {
+              bf16x4 ov;
+              ov[0] = (bf16)t[u].x; ov[1] = (bf16)t[u].y; ov[2] = (bf16)t[u].z; ov[3] = (bf16)t[u].w;
+              *(bf16x4*)((bf16*)Cb + zc + (long)rows[u] * g.ldc + cols[u]) = ov;
+            }
         }
       }
     }
-    __syncthreads();
-  }
+    __builtin_amdgcn_wave_barrier();
+  };
+  store_block(std::integral_constant<int, 0>{});
+  if constexpr (MI > 1) store_block(std::integral_constant<int, 1>{});
+  if constexpr (MI > 2) store_block(std::integral_constant<int, 2>{});
+  if constexpr (MI > 3) store_block(std::integral_constant<int, 3>{});
+  static_assert(MI <= 4, "at most four 32-row blocks per wave");
 }
 
+// explicit instantiations (every tile shape x operand layout the launcher can pick)
+#define DAPPLE_GEMM_INST(BM, BN, WGM, WGN)                                                        \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, false, false>(GemmArgs, int, int); \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, false, true>(GemmArgs, int, int);  \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, true, false>(GemmArgs, int, int);  \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, true, true>(GemmArgs, int, int);
+DAPPLE_GEMM_INST(256, 256, 2, 2)
+DAPPLE_GEMM_INST(256, 128, 2, 2)
+DAPPLE_GEMM_INST(128, 128, 2, 2)
+DAPPLE_GEMM_INST(128, 64, 2, 2)
+#undef DAPPLE_GEMM_INST
+
 // ------------------------------------------------------------------ host side
-template <int BM, int BN, bool AKS, bool BKS>
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
 static hipError_t launch_mfma(const GemmArgs& g, hipStream_t st) {
-  typedef GemmTile<BM, BN, AKS, BKS> CFG;
+  typedef GemmTile<BM, BN, WGM, WGN, AKS, BKS> CFG;
   static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<BM, BN, AKS, BKS>;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, AKS, BKS>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)CFG::LDS_BYTES);
@@ -285,16 +416,18 @@ static hipError_t launch_mfma(const GemmArgs& g, hipStream_t st) {
   }
   int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   dim3 grid(tiles_m * tiles_n, 1, g.batch);
-  hipLaunchKernelGGL(kern, grid, dim3(256), CFG::LDS_BYTES, st, g, tiles_m, tiles_n);
+  hipLaunchKernelGGL(kern, grid, dim3(CFG::NT), CFG::LDS_BYTES, st, g, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int WGM, int WGN>
 static hipError_t launch_mfma_layout(const GemmArgs& g, hipStream_t st) {
   if (g.a_kstrided) {
-    return g.b_kstrided ? launch_mfma<BM, BN, true, true>(g, st) : launch_mfma<BM, BN, true, false>(g, st);
+    return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, true, true>(g, st)
+                        : launch_mfma<BM, BN, WGM, WGN, true, false>(g, st);
   }
-  return g.b_kstrided ? launch_mfma<BM, BN, false, true>(g, st) : launch_mfma<BM, BN, false, false>(g, st);
+  return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, false, true>(g, st)
+                      : launch_mfma<BM, BN, WGM, WGN, false, false>(g, st);
 }
 
 static bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
@@ -302,7 +435,7 @@ static bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0
 bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
   if (dt != DT_BF16) return false;
   if (g.K < BK || g.K % BK || g.kseg_len % BK || g.K % g.kseg_len) return false;
-  if (g.lda % 8 || g.ldb % 8 || g.ldc % 4) return false;
+  if (g.lda % 8 || g.ldb % 8 || g.ldc % 4 || g.N % 4) return false;
   if (g.sA % 8 || g.sB % 8 || g.sC % 4 || g.sBias % 4 || g.segA % 8 || g.segB % 8) return false;
   if (!aligned_to(g.A, 16) || !aligned_to(g.B, 16) || !aligned_to(g.C, 16)) return false;
   if (g.a_kstrided && g.M % 8) return false;
@@ -316,12 +449,17 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
 hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;
   if (gemm_uses_mfma(dt, g)) {
-    // tile choice: the largest tile that still gives every CU work
-    long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
-    long t2x1 = (long)((g.M + 255) / 256) * ((g.N + 127) / 128) * g.batch;
-    if (t256 >= 256) return launch_mfma_layout<256, 256>(g, st);
-    if (t2x1 >= 256) return launch_mfma_layout<256, 128>(g, st);
-    return launch_mfma_layout<128, 128>(g, st);
+    // tuning override: DAPPLE_GEMM_TILE = 0 (256x256, 4 waves), 1 (256x128), 2 (128x128), 3 (128x64)
+    static const int force = [] { const char* e = getenv("DAPPLE_GEMM_TILE"); return e ? atoi(e) : -1; }();
+    if (force == 0) return launch_mfma_layout<256, 256, 2, 2>(g, st);
+    if (force == 1) return launch_mfma_layout<256, 128, 2, 2>(g, st);
+    if (force == 2) return launch_mfma_layout<128, 128, 2, 2>(g, st);
+    if (force == 3) return launch_mfma_layout<128, 64, 2, 2>(g, st);
+    // tile choice (measured on the BERT-Large-shaped stage): 128x128 tiles when they give
+    // every CU at least two workgroups, else 128x64 tiles to keep all CUs busy
+    long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
+    if (t128 >= 512) return launch_mfma_layout<128, 128, 2, 2>(g, st);
+    return launch_mfma_layout<128, 64, 2, 2>(g, st);
   }
   dim3 blk(32, 8);
   dim3 grid((g.N + 31) / 32, (g.M + 7) / 8, g.batch);

@@ -38,6 +38,12 @@ struct GemmArgs {
   long segA, segB;
   int batch;
   long sA, sB, sC, sBias;
+  // optional per-instance operand pointers (batch <= 4); when Az[0] / Bz[0] / Cz[0] is set
+  // they replace A + z*sA / B + z*sB / C + z*sC, so unrelated products of one shape can
+  // share a launch
+  const void* Az[4];
+  const void* Bz[4];
+  void* Cz[4];
   int k_valid;  // k-strided operands: rows k >= k_valid read as zero (K itself is padded)
   int epi;
 };
