@@ -71,7 +71,7 @@ int dapple_attention_bwd(int dtype, const void* q, const void* k, const void* v,
 int dapple_layernorm_fwd(int dtype, const void* z, const void* gamma, const void* beta, void* y,
                          float* stats, int rows, int H, float eps, void* stream);
 /* dz from dy; dgamma += sum_r dy*xhat, dbeta += sum_r dy, dbias += sum_r dz (each
- * fp32 [H], NULL to skip).  partial: fp32 scratch of ceil(rows/16)*3*H elements. */
+ * fp32 [H], NULL to skip).  partial: fp32 scratch of ceil(rows/8)*3*H elements. */
 int dapple_layernorm_bwd(int dtype, const void* dy, const void* z, const float* stats, const void* gamma,
                          void* dz, float* partial, float* dgamma, float* dbeta, float* dbias, int rows,
                          int H, void* stream);

@@ -105,29 +105,54 @@ __global__ void attn_bwd_plain(AttnArgs a, float scale2, float scale, int which)
 }
 
 // ------------------------------------------------------------------ MFMA kernels
-constexpr int AD = 64;        // head dimension
-constexpr int ALD = AD + 16;  // LDS row stride in elements (160 bytes)
+constexpr int AD = 64;  // head dimension
 
-// copy a 64 x 64 bf16 block (row stride ldg) into LDS [64][ALD]; 256 threads
-__device__ __forceinline__ void load_block64(bf16* S, const bf16* g, int ldg, int tid) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    int c = tid + 256 * i;
-    int r = c >> 3, kc = c & 7;
-    *(uint4*)(S + r * ALD + kc * 8) = *(const uint4*)(g + (long)r * ldg + kc * 8);
-  }
+// A 64 x 64 bf16 block sits in LDS as 64 rows of 128 bytes with the 16-byte chunks of row
+// r XOR-swizzled by aswz(r).  The same block is read two ways -- 128-bit reads along a
+// row (16 lanes = 16 rows at a time) and transpose reads down the rows (32 lanes = 4 rows
+// x 64 bytes at a time) -- and LDS has 64 four-byte banks, so either group must cover 256
+// distinct bytes modulo 256: rows of equal parity need distinct chunks (a bijection of
+// (r>>1)&7), and rows r and r+2 must land in different 64-byte halves (bit 2 of the
+// swizzle = bit 1 of r).  Rotating the three bits of (r>>1)&7 right by one gives both.
+__device__ __forceinline__ int aswz(int r) {
+  int x = (r >> 1) & 7;
+  return ((x & 1) << 2) | (x >> 1);
 }
+
+// a 64 x 64 block in flight from global memory: 2 chunks of 16 bytes per thread (256 threads)
+struct Block64 {
+  uint4 c[2];
+  __device__ __forceinline__ void load(const bf16* g, int ldg, int tid) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      int ch = tid + 256 * i;
+      c[i] = *(const uint4*)(g + (long)(ch >> 3) * ldg + (ch & 7) * 8);
+    }
+  }
+  __device__ __forceinline__ void store(bf16* S, int tid) const {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      int ch = tid + 256 * i;
+      int r = ch >> 3, kc = ch & 7;
+      *(uint4*)(S + r * AD + ((kc ^ aswz(r)) << 3)) = c[i];
+    }
+  }
+};
 // operand fragment, contraction index contiguous in LDS: rows r0 + (lane&31), k = 16 kk + 8 (lane>>5) + e
 __device__ __forceinline__ bf16x8 frag_rows(const bf16* S, int r0, int kk, int lane) {
-  return *(const bf16x8*)(S + (r0 + (lane & 31)) * ALD + kk * 16 + 8 * (lane >> 5));
+  int r = r0 + (lane & 31), kc = kk * 2 + (lane >> 5);
+  return *(const bf16x8*)(S + r * AD + ((kc ^ aswz(r)) << 3));
 }
 // operand fragment, contraction index along LDS rows: column c0 + (lane&31); element e < 4 is
 // LDS row k0 + 4 (lane>>5) + e, element 4 + e is LDS row k0 + 8 + 4 (lane>>5) + e -- the order
 // in which a 32x32 accumulator hands its rows to a lane
 __device__ __forceinline__ bf16x8 frag_cols(const bf16* S, int c0, int k0, int lane) {
   int i16 = lane & 15, g16 = (lane >> 4) & 1, h = lane >> 5;
-  const bf16* p = S + (k0 + 4 * h + (i16 >> 2)) * ALD + c0 + 16 * g16 + 4 * (i16 & 3);
-  return join8(lds_read_tr16(p), lds_read_tr16(p + 8 * ALD));
+  int r = k0 + 4 * h + (i16 >> 2);
+  int col = c0 + 16 * g16 + 4 * (i16 & 3);
+  const bf16* p0 = S + r * AD + (((col >> 3) ^ aswz(r)) << 3) + (col & 7);
+  const bf16* p1 = S + (r + 8) * AD + (((col >> 3) ^ aswz(r + 8)) << 3) + (col & 7);
+  return join8(lds_read_tr16(p0), lds_read_tr16(p1));
 }
 // global fragment of a row the wave owns: row r (or zeros), k = 16 kk + 8 (lane>>5) + e
 __device__ __forceinline__ bf16x8 frag_global(const bf16* base, long row, bool ok, int ld, int kk, int lane) {
@@ -160,14 +185,18 @@ __device__ __forceinline__ f32x16 zero16() {
 }
 
 __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnArgs a, float scale2) {
-  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * ALD];
-  __shared__ __attribute__((aligned(16))) bf16 Vs[64 * ALD];
+  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * AD];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[64 * AD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
   const int bi = blockIdx.y / a.A, hh = blockIdx.y % a.A;
   const long hb = (long)bi * a.s * a.H + hh * AD;
   const bf16 *Q = (const bf16*)a.q + hb, *K = (const bf16*)a.k + hb, *V = (const bf16*)a.v + hb;
   const int qrow = blockIdx.x * 128 + wave * 32 + (lane & 31);
   const bool qok = qrow < a.s;
+  const int nkb = a.s / 64;
+  Block64 kblk, vblk;  // the next key/value block, in flight while the current one is used
+  kblk.load(K, a.H, tid);
+  vblk.load(V, a.H, tid);
 
   bf16x8 qf[4];
 #pragma unroll
@@ -176,11 +205,15 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnArgs a, float scale2) {
   float m = -INFINITY, l = 0.f;
   f32x16 o[2] = {zero16(), zero16()};  // rows d = 32 dblk + 8 blk + 4 h + e, column = the lane's query
 
-  for (int kb = 0; kb < a.s / 64; ++kb) {
+  for (int kb = 0; kb < nkb; ++kb) {
     __syncthreads();
-    load_block64(Ks, K + (long)kb * 64 * a.H, a.H, tid);
-    load_block64(Vs, V + (long)kb * 64 * a.H, a.H, tid);
+    kblk.store(Ks, tid);
+    vblk.store(Vs, tid);
     __syncthreads();
+    if (kb + 1 < nkb) {
+      kblk.load(K + (long)(kb + 1) * 64 * a.H, a.H, tid);
+      vblk.load(V + (long)(kb + 1) * 64 * a.H, a.H, tid);
+    }
     float p[2][16];
     float mx = -INFINITY;
 #pragma unroll
@@ -237,8 +270,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnArgs a, float scale2) {
 
 // dk, dv: the wave owns 32 key rows; query blocks of 64 stream through LDS
 __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, float scale) {
-  __shared__ __attribute__((aligned(16))) bf16 Qs[64 * ALD];
-  __shared__ __attribute__((aligned(16))) bf16 Gs[64 * ALD];
+  __shared__ __attribute__((aligned(16))) bf16 Qs[64 * AD];
+  __shared__ __attribute__((aligned(16))) bf16 Gs[64 * AD];
   __shared__ __attribute__((aligned(16))) float Ls[64];
   __shared__ __attribute__((aligned(16))) float Ds[64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
@@ -258,14 +291,24 @@ __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, 
     vf[kk] = frag_global(V, krow, kok, a.H, kk, lane);
   }
   f32x16 dv[2] = {zero16(), zero16()}, dk[2] = {zero16(), zero16()};  // rows d, column = the lane's key
+  const int nqb = a.s / 64;
+  Block64 qblk, gblk;  // the next query / dctx block, in flight while the current one is used
+  qblk.load(Q, a.H, tid);
+  gblk.load(G, a.H, tid);
+  float stat = tid < 64 ? lse[tid] : (tid < 128 ? dl[tid - 64] : 0.f);
 
-  for (int qb = 0; qb < a.s / 64; ++qb) {
+  for (int qb = 0; qb < nqb; ++qb) {
     __syncthreads();
-    load_block64(Qs, Q + (long)qb * 64 * a.H, a.H, tid);
-    load_block64(Gs, G + (long)qb * 64 * a.H, a.H, tid);
-    if (tid < 64) Ls[tid] = lse[qb * 64 + tid];
-    else if (tid < 128) Ds[tid - 64] = dl[qb * 64 + tid - 64];
+    qblk.store(Qs, tid);
+    gblk.store(Gs, tid);
+    if (tid < 64) Ls[tid] = stat;
+    else if (tid < 128) Ds[tid - 64] = stat;
     __syncthreads();
+    if (qb + 1 < nqb) {
+      qblk.load(Q + (long)(qb + 1) * 64 * a.H, a.H, tid);
+      gblk.load(G + (long)(qb + 1) * 64 * a.H, a.H, tid);
+      stat = tid < 64 ? lse[(qb + 1) * 64 + tid] : (tid < 128 ? dl[(qb + 1) * 64 + tid - 64] : 0.f);
+    }
 #pragma unroll
     for (int qb2 = 0; qb2 < 2; ++qb2) {
       f32x16 sa = zero16(), dp = zero16();  // rows: query 32 qb2 + 8 blk + 4 h + e, column: key
@@ -319,8 +362,8 @@ __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, 
 
 // dq: the wave owns 32 query rows; key blocks of 64 stream through LDS
 __global__ __launch_bounds__(256) void attn_dq_mfma(AttnArgs a, float scale2, float scale) {
-  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * ALD];
-  __shared__ __attribute__((aligned(16))) bf16 Vs[64 * ALD];
+  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * AD];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[64 * AD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
   const int bi = blockIdx.y / a.A, hh = blockIdx.y % a.A;
   const long hb = (long)bi * a.s * a.H + hh * AD;
@@ -329,21 +372,37 @@ __global__ __launch_bounds__(256) void attn_dq_mfma(AttnArgs a, float scale2, fl
   const int qrow = blockIdx.x * 128 + wave * 32 + (lane & 31);
   const bool qok = qrow < a.s;
   const float Lq = qok ? a.lse[((long)bi * a.A + hh) * a.s + qrow] : 0.f;
-  const float Dq = qok ? a.delta[((long)bi * a.A + hh) * a.s + qrow] : 0.f;
 
   bf16x8 qf[4], gf[4];
+  // delta = rowsum(dctx o ctx) of the lane's query row: each half-wave holds 32 of the 64
+  // head columns; the sum is published for the dk/dv kernel, which runs after this one
+  const bf16* O = (const bf16*)a.ctx + hb;
+  float Dq = 0.f;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     qf[kk] = frag_global(Q, qrow, qok, a.H, kk, lane);
     gf[kk] = frag_global(G, qrow, qok, a.H, kk, lane);
+    bf16x8 of = frag_global(O, qrow, qok, a.H, kk, lane);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) Dq = fmaf((float)gf[kk][e], (float)of[e], Dq);
   }
+  Dq += __shfl_xor(Dq, 32, 64);
+  if (qok && h == 0) a.delta[((long)bi * a.A + hh) * a.s + qrow] = Dq;
   f32x16 dq[2] = {zero16(), zero16()};  // rows d, column = the lane's query
+  const int nkb = a.s / 64;
+  Block64 kblk, vblk;
+  kblk.load(K, a.H, tid);
+  vblk.load(V, a.H, tid);
 
-  for (int kb = 0; kb < a.s / 64; ++kb) {
+  for (int kb = 0; kb < nkb; ++kb) {
     __syncthreads();
-    load_block64(Ks, K + (long)kb * 64 * a.H, a.H, tid);
-    load_block64(Vs, V + (long)kb * 64 * a.H, a.H, tid);
+    kblk.store(Ks, tid);
+    vblk.store(Vs, tid);
     __syncthreads();
+    if (kb + 1 < nkb) {
+      kblk.load(K + (long)(kb + 1) * 64 * a.H, a.H, tid);
+      vblk.load(V + (long)(kb + 1) * 64 * a.H, a.H, tid);
+    }
 #pragma unroll
     for (int kb2 = 0; kb2 < 2; ++kb2) {
       f32x16 sa = zero16(), dp = zero16();  // rows: key 32 kb2 + 8 blk + 4 h + e, column: query
@@ -402,20 +461,22 @@ hipError_t launch_attn_fwd(Dtype dt, const AttnArgs& a, hipStream_t st) {
 
 hipError_t launch_attn_bwd(Dtype dt, const AttnArgs& a, hipStream_t st) {
   float scale = 1.0f / sqrtf((float)a.d), scale2 = LOG2E * scale;
+  hipError_t e;
+  if (attn_uses_mfma(dt, a)) {
+    // dq first: it also writes delta, which dk/dv reads
+    dim3 grid((a.s + 127) / 128, a.b * a.A);
+    hipLaunchKernelGGL(attn_dq_mfma, grid, dim3(256), 0, st, a, scale2, scale);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(attn_dkdv_mfma, grid, dim3(256), 0, st, a, scale2, scale);
+    return hipGetLastError();
+  }
   long nd = (long)a.b * a.s * a.A;
   dim3 gd((unsigned)((nd + 255) / 256));
   if (dt == DT_BF16) hipLaunchKernelGGL(attn_delta_kernel<bf16>, gd, dim3(256), 0, st, a);
   else hipLaunchKernelGGL(attn_delta_kernel<float>, gd, dim3(256), 0, st, a);
-  hipError_t e = hipGetLastError();
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (attn_uses_mfma(dt, a)) {
-    dim3 grid((a.s + 127) / 128, a.b * a.A);
-    hipLaunchKernelGGL(attn_dkdv_mfma, grid, dim3(256), 0, st, a, scale2, scale);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_dq_mfma, grid, dim3(256), 0, st, a, scale2, scale);
-    return hipGetLastError();
-  }
   long total = (long)a.b * a.A * a.s * a.d;
   dim3 grid((unsigned)((total + 255) / 256));
   for (int which = 0; which < 3; ++which) {

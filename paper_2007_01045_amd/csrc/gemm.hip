@@ -30,8 +30,10 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs& g, long zc, long 
   if (g.epi & EPI_MUL) t *= to_f32(((const T*)g.aux)[zc + (long)row * g.ldaux + col]);
   long o = zc + (long)row * g.ldc + col;
   if (g.epi & EPI_GELU) {
-    ((T*)g.C)[o] = from_f32<T>(gelu_f(t));
-    ((T*)g.C2)[o] = from_f32<T>(gelu_grad_f(t));
+    float a, b;
+    gelu_both(t, a, b);
+    ((T*)g.C)[o] = from_f32<T>(a);
+    ((T*)g.C2)[o] = from_f32<T>(b);
   } else if (g.epi & EPI_ACC32) {
     ((float*)g.C)[o] += t;
   } else {
@@ -71,7 +73,7 @@ __global__ void gemm_plain_kernel(GemmArgs g) {
 constexpr int BK = 64;
 constexpr unsigned BUF_RSRC_FLAGS = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int int4v;
 
 // One operand's [R x 64] tile of a k-step in LDS, filled by buffer loads that
 // write straight into LDS (16 bytes per lane, 1 KiB contiguous per wave
@@ -113,10 +115,25 @@ struct OperandTile {
   // operand + k0*ld); avail: bytes from base to the end of the valid operand region
   __device__ __forceinline__ void load(const bf16* base, long avail, bf16* S, int wave) const {
     unsigned rec = avail <= 0 ? 0u : (avail > 0x7fffffffL ? 0x7fffffffu : (unsigned)avail);
-    __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, rec, BUF_RSRC_FLAGS);
+    // buffer resource: base address, stride 0, num_records (bytes), raw 32-bit format
+    uint64_t b = (uint64_t)base;
+    int4v rs;
+    rs[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    rs[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(b >> 32) & 0xffffu));
+    rs[2] = __builtin_amdgcn_readfirstlane((int)rec);
+    rs[3] = (int)BUF_RSRC_FLAGS;
+    // The loads are issued from inline assembly on purpose: through the compiler builtin
+    // every LDS read that follows waits for ALL outstanding loads (the compiler cannot tell
+    // the ring slots apart), which would undo the multi-stage pipeline.  The kernel keeps
+    // its own count instead (s_waitcnt vmcnt(n) before the workgroup barrier).
 #pragma unroll
-    for (int j = 0; j < NI; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(S + (j * NW + wave) * 512), 16, voff[j], 0, 0, 0);
+    for (int j = 0; j < NI; ++j) {
+      unsigned dst = (unsigned)(uintptr_t)(S + (j * NW + wave) * 512);
+      asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :
+                   : "s"(__builtin_amdgcn_readfirstlane((int)dst)), "v"(voff[j]), "s"(rs)
+                   : "memory", "m0");
+    }
   }
   // MFMA fragment for rows r0..r0+31 (lane & 31), k = kk*16 + 8*(lane>>5) + 0..7
   static __device__ __forceinline__ bf16x8 frag(const bf16* S, int r0, int kk, int lane) {
@@ -135,7 +152,7 @@ struct OperandTile {
   }
 };
 
-template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS>
 struct GemmTile {
   static constexpr int NW = WGM * WGN, NT = 64 * NW;
   static constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
@@ -143,14 +160,15 @@ struct GemmTile {
   typedef OperandTile<BN, BKS, NW> TB;
   static constexpr int STAGE_ELEMS = TA::LDS_ELEMS + TB::LDS_ELEMS;
   static constexpr int EPI_LD = WN + 4;  // fp32 staging row
-  static constexpr size_t MAIN_BYTES = 2 * (size_t)STAGE_ELEMS * sizeof(bf16);
+  static constexpr size_t MAIN_BYTES = NS * (size_t)STAGE_ELEMS * sizeof(bf16);
+  static constexpr int LOADS_PER_TILE = TA::NI + TB::NI;  // per wave
   static constexpr size_t EPI_BYTES = (size_t)NW * 32 * EPI_LD * sizeof(float);
   static constexpr size_t LDS_BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
 };
 
-template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
-  typedef GemmTile<BM, BN, WGM, WGN, AKS, BKS> CFG;
+  typedef GemmTile<BM, BN, WGM, WGN, NS, AKS, BKS> CFG;
   typedef typename CFG::TA TA;
   typedef typename CFG::TB TB;
   constexpr int MI = CFG::MI, NI = CFG::NI;
@@ -206,14 +224,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   ta.init(g.lda, m0, wave, lane);
   tb.init(g.ldb, n0, wave, lane);
 
+  // request k-tile kt into ring slot kt % NS; a tile past the end requests nothing (zero
+  // records: every lane is out of range), which keeps the number of outstanding requests
+  // per tile constant so that one s_waitcnt count fits every iteration
   auto issue_loads = [&](int kt) {
     int seg = kt / tiles_per_seg;
     int k0 = (kt - seg * tiles_per_seg) * BK;
     long aoff = AKS ? (long)k0 * g.lda : (long)k0;
     long boff = BKS ? (long)k0 * g.ldb : (long)k0;
-    bf16* S = lds + (kt & 1) * CFG::STAGE_ELEMS;
-    ta.load(Ab + seg * g.segA + aoff, a_ext - aoff * 2, S, wave);
-    tb.load(Bb + seg * g.segB + boff, b_ext - boff * 2, S + TA::LDS_ELEMS, wave);
+    bf16* S = lds + (kt % NS) * CFG::STAGE_ELEMS;
+    bool live = kt < nk;
+    ta.load(Ab + (live ? seg * g.segA + aoff : 0), live ? a_ext - aoff * 2 : 0, S, wave);
+    tb.load(Bb + (live ? seg * g.segB + boff : 0), live ? b_ext - boff * 2 : 0, S + TA::LDS_ELEMS, wave);
   };
 
   f32x16 acc[MI][NI];
@@ -247,37 +269,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
   };
 
-  issue_loads(0);
-  if (nk > 1) issue_loads(1);
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
-  __syncthreads();
-  Frags cur, nxt;
-  load_frags(cur, lds, 0);
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const bf16* As = lds + (kt & 1) * CFG::STAGE_ELEMS;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16 - 1; ++kk) {
-      load_frags(nxt, As, kk + 1);
+  for (int t = 0; t < NS - 1; ++t) issue_loads(t);
+
+  // vmcnt(N): at most N of this wave's requests still in flight; requests complete in
+  // order, so N = (NS - 2) * LOADS_PER_TILE means "tile kt has landed"
+  constexpr int INFLIGHT = (NS - 2) * CFG::LOADS_PER_TILE;
+  static_assert(INFLIGHT < 64, "vmcnt is a 6-bit counter");
+  constexpr int WAIT_TILE = (INFLIGHT & 15) | ((INFLIGHT >> 4) << 14) | 0x0F70;  // expcnt, lgkmcnt: no wait
+
+  Frags cur, nxt;
+  for (int kt = 0; kt < nk; ++kt) {
+    const bf16* As = lds + (kt % NS) * CFG::STAGE_ELEMS;
+    __builtin_amdgcn_s_waitcnt(WAIT_TILE);
+    __builtin_amdgcn_s_barrier();  // every wave's part of tile kt is in LDS; tile kt-1's slot is free
+    issue_loads(kt + NS - 1);
+    load_frags(cur, As, 0);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      if (kk + 1 < BK / 16) load_frags(nxt, As, kk + 1);
       __builtin_amdgcn_sched_barrier(0);
       mfma_step(cur);
       __builtin_amdgcn_sched_barrier(0);
       cur = nxt;
     }
-    // cur holds the last k-step of this tile: the buffer is no longer needed
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-    if (kt + 1 < nk) load_frags(nxt, lds + ((kt + 1) & 1) * CFG::STAGE_ELEMS, 0);
-    if (kt + 2 < nk) issue_loads(kt + 2);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_step(cur);
-    __builtin_amdgcn_sched_barrier(0);
-    cur = nxt;
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) tail requests before LDS is reused
   __syncthreads();
 
-  // epilogue: per wave, 32 output rows at a time through an fp32 LDS staging tile.
-  // acc[i][j][v]: row = wm0 + 32 i + (lane & 31), col = wn0 + 32 j + 8 (v>>2) + 4 (lane>>5) + (v&3)
   // epilogue: per wave, 32 output rows at a time through an fp32 LDS staging tile that
   // turns "a lane owns 4 columns of one row" into row-contiguous stores.
   // acc[i][j][v]: row = wm0 + 32 i + (lane & 31), col = wn0 + 32 j + 8 (v>>2) + 4 (lane>>5) + (v&3)
@@ -363,8 +382,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
               bf16x4 gv, gp;
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
-                gv[e] = (bf16)gelu_f(tv[e]);
-                gp[e] = (bf16)gelu_grad_f(tv[e]);
+                float a, b;
+                gelu_both(tv[e], a, b);
+                gv[e] = (bf16)a;
+                gp[e] = (bf16)b;
               }
               long o = zc + (long)rows[u] * g.ldc + cols[u];
               *(bf16x4*)((bf16*)Cb + o) = gv;
@@ -391,23 +412,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
 }
 
 // explicit instantiations (every tile shape x operand layout the launcher can pick)
-#define DAPPLE_GEMM_INST(BM, BN, WGM, WGN)                                                        \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, false, false>(GemmArgs, int, int); \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, false, true>(GemmArgs, int, int);  \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, true, false>(GemmArgs, int, int);  \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, true, true>(GemmArgs, int, int);
-DAPPLE_GEMM_INST(256, 256, 2, 2)
-DAPPLE_GEMM_INST(256, 128, 2, 2)
-DAPPLE_GEMM_INST(128, 128, 2, 2)
-DAPPLE_GEMM_INST(128, 64, 2, 2)
+#define DAPPLE_GEMM_INST(BM, BN, WGM, WGN, NS)                                                        \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, false>(GemmArgs, int, int); \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, true>(GemmArgs, int, int);  \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, false>(GemmArgs, int, int);  \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, true>(GemmArgs, int, int);
+DAPPLE_GEMM_INST(256, 256, 2, 2, 2)
+DAPPLE_GEMM_INST(256, 128, 2, 2, 3)
+DAPPLE_GEMM_INST(128, 128, 2, 2, 2)
+DAPPLE_GEMM_INST(128, 128, 2, 2, 4)
+DAPPLE_GEMM_INST(128, 64, 2, 2, 3)
+DAPPLE_GEMM_INST(128, 64, 2, 2, 6)
 #undef DAPPLE_GEMM_INST
 
 // ------------------------------------------------------------------ host side
-template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS>
 static hipError_t launch_mfma(const GemmArgs& g, hipStream_t st) {
-  typedef GemmTile<BM, BN, WGM, WGN, AKS, BKS> CFG;
+  typedef GemmTile<BM, BN, WGM, WGN, NS, AKS, BKS> CFG;
   static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, AKS, BKS>;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, NS, AKS, BKS>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)CFG::LDS_BYTES);
@@ -420,14 +443,14 @@ static hipError_t launch_mfma(const GemmArgs& g, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int NS>
 static hipError_t launch_mfma_layout(const GemmArgs& g, hipStream_t st) {
   if (g.a_kstrided) {
-    return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, true, true>(g, st)
-                        : launch_mfma<BM, BN, WGM, WGN, true, false>(g, st);
+    return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, NS, true, true>(g, st)
+                        : launch_mfma<BM, BN, WGM, WGN, NS, true, false>(g, st);
   }
-  return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, false, true>(g, st)
-                      : launch_mfma<BM, BN, WGM, WGN, false, false>(g, st);
+  return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, NS, false, true>(g, st)
+                      : launch_mfma<BM, BN, WGM, WGN, NS, false, false>(g, st);
 }
 
 static bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
@@ -438,6 +461,13 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
   if (g.lda % 8 || g.ldb % 8 || g.ldc % 4 || g.N % 4) return false;
   if (g.sA % 8 || g.sB % 8 || g.sC % 4 || g.sBias % 4 || g.segA % 8 || g.segB % 8) return false;
   if (!aligned_to(g.A, 16) || !aligned_to(g.B, 16) || !aligned_to(g.C, 16)) return false;
+  if (g.Az[0] || g.Bz[0] || g.Cz[0]) {
+    if (g.batch > 4) return false;
+    for (int z = 0; z < g.batch; ++z)
+      if (!g.Az[z] || !g.Bz[z] || !g.Cz[z] || !aligned_to(g.Az[z], 16) || !aligned_to(g.Bz[z], 16) ||
+          !aligned_to(g.Cz[z], 16))
+        return false;
+  }
   if (g.a_kstrided && g.M % 8) return false;
   if (g.b_kstrided && g.N % 8) return false;
   if ((g.epi & (EPI_ADD | EPI_MUL)) && (g.ldaux % 4 || !aligned_to(g.aux, 8))) return false;
@@ -451,15 +481,18 @@ hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st) {
   if (gemm_uses_mfma(dt, g)) {
     // tuning override: DAPPLE_GEMM_TILE = 0 (256x256, 4 waves), 1 (256x128), 2 (128x128), 3 (128x64)
     static const int force = [] { const char* e = getenv("DAPPLE_GEMM_TILE"); return e ? atoi(e) : -1; }();
-    if (force == 0) return launch_mfma_layout<256, 256, 2, 2>(g, st);
-    if (force == 1) return launch_mfma_layout<256, 128, 2, 2>(g, st);
-    if (force == 2) return launch_mfma_layout<128, 128, 2, 2>(g, st);
-    if (force == 3) return launch_mfma_layout<128, 64, 2, 2>(g, st);
-    // tile choice (measured on the BERT-Large-shaped stage): 128x128 tiles when they give
-    // every CU at least two workgroups, else 128x64 tiles to keep all CUs busy
+    if (force == 0) return launch_mfma_layout<256, 256, 2, 2, 2>(g, st);
+    if (force == 1) return launch_mfma_layout<256, 128, 2, 2, 3>(g, st);
+    if (force == 2) return launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
+    if (force == 3) return launch_mfma_layout<128, 64, 2, 2, 3>(g, st);
+    if (force == 4) return launch_mfma_layout<128, 128, 2, 2, 4>(g, st);
+    if (force == 5) return launch_mfma_layout<128, 64, 2, 2, 6>(g, st);
+    // tile choice (measured on the BERT-Large-shaped stage): 128x128 tiles (two LDS stages,
+    // two workgroups per CU) when there are at least 192 of them, else 128x64 tiles with a
+    // three-stage ring to keep all CUs busy
     long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
-    if (t128 >= 512) return launch_mfma_layout<128, 128, 2, 2>(g, st);
-    return launch_mfma_layout<128, 64, 2, 2>(g, st);
+    if (t128 >= 192) return launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
+    return launch_mfma_layout<128, 64, 2, 2, 3>(g, st);
   }
   dim3 blk(32, 8);
   dim3 grid((g.N + 31) / 32, (g.M + 7) / 8, g.batch);

@@ -81,7 +81,7 @@ int dapple_colsum(int dtype, const void* X, int rows, int cols, int ld, float* p
   if (!X || !partial || !out) return STAGE_E_NULL;
   int vec = dtype == STAGE_DTYPE_BF16 ? 8 : 4;
   if (bad_dtype(dtype) || rows < 1 || cols < 1 || cols % vec || ld % vec) return STAGE_E_CONFIG;
-  return dev_rc(launch_colsum(dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32, X, rows, cols, ld, partial, out,
+  return dev_rc(launch_colsum(dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32, X, rows, cols, ld, partial, out, 1, 0, 0,
                               (hipStream_t)stream));
 }
 

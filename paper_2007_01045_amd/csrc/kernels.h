@@ -83,9 +83,10 @@ hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, const float* s
 // a NULL o_v is skipped
 hipError_t launch_partial_reduce(const float* partial, int nblk, int nvec, int H, float* o0,
                                  float* o1, float* o2, hipStream_t st);
-// out[c] += sum_r X[r*ld + c]  (two fixed-order stages through `partial`)
+// out[c] += sum_r X[r*ld + c]  (two fixed-order stages through `partial`); nb instances at
+// element strides zs_x (X) and zs_out (out); partial needs nb * ceil(rows/64) * cols floats
 hipError_t launch_colsum(Dtype dt, const void* X, int rows, int cols, int ld, float* partial,
-                         float* out, hipStream_t st);
+                         float* out, int nb, long zs_x, long zs_out, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_zero(void* dst, size_t bytes, hipStream_t st);
 

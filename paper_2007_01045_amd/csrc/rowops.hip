@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ z, co
 // A block takes LNB_ROWS consecutive rows (each wave every 4th of them), keeps the
 // per-column partial sums of dy*xhat, dy and dz in registers, combines the four
 // waves in LDS in wave order and writes partial[(blk*3 + v)*H + col].
-constexpr int LNB_ROWS = 16;
+constexpr int LNB_ROWS = 8;
 
 template <typename T, int NCH>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ z,
@@ -113,25 +113,43 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
     for (int e = 0; e < V; ++e) pg[c][e] = pb[c][e] = pz[c][e] = g[c][e] = 0.f;
     if (col < H) load_vec<T>(gamma + col, g[c]);
   }
-  for (int rr = wave; rr < LNB_ROWS; rr += 4) {
-    int row = blockIdx.x * LNB_ROWS + rr;
-    if (row >= rows) break;
-    float mean = stats[2 * row], rstd = stats[2 * row + 1];
-    float d[NCH][V], xh[NCH][V];
+  // each wave takes rows wave, wave + 4, ...; the loads of all its rows are issued first
+  constexpr int RPW = LNB_ROWS / 4;
+  float d[RPW][NCH][V], zz[RPW][NCH][V], mean[RPW], rstd[RPW];
+  bool live[RPW];
+#pragma unroll
+  for (int q = 0; q < RPW; ++q) {
+    int row = blockIdx.x * LNB_ROWS + wave + 4 * q;
+    live[q] = row < rows;
+    mean[q] = live[q] ? stats[2 * row] : 0.f;
+    rstd[q] = live[q] ? stats[2 * row + 1] : 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      int col = (c * 64 + lane) * V;
+      if (live[q] && col < H) {
+        load_vec<T>(dy + (long)row * H + col, d[q][c]);
+        load_vec<T>(z + (long)row * H + col, zz[q][c]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < V; ++e) d[q][c][e] = zz[q][c][e] = 0.f;
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < RPW; ++q) {
+    if (!live[q]) continue;
+    int row = blockIdx.x * LNB_ROWS + wave + 4 * q;
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
       int col = (c * 64 + lane) * V;
       if (col < H) {
-        float zz[V];
-        load_vec<T>(dy + (long)row * H + col, d[c]);
-        load_vec<T>(z + (long)row * H + col, zz);
 #pragma unroll
         for (int e = 0; e < V; ++e) {
-          xh[c][e] = (zz[e] - mean) * rstd;
-          float dxh = d[c][e] * g[c][e];
+          zz[q][c][e] = (zz[q][c][e] - mean[q]) * rstd[q];  // x-hat
+          float dxh = d[q][c][e] * g[c][e];
           s1 += dxh;
-          s2 += dxh * xh[c][e];
+          s2 += dxh * zz[q][c][e];
         }
       }
     }
@@ -143,9 +161,9 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
         float o[V];
 #pragma unroll
         for (int e = 0; e < V; ++e) {
-          o[e] = rstd * (d[c][e] * g[c][e] - m1 - xh[c][e] * m2);
-          pg[c][e] += d[c][e] * xh[c][e];
-          pb[c][e] += d[c][e];
+          o[e] = rstd[q] * (d[q][c][e] * g[c][e] - m1 - zz[q][c][e] * m2);
+          pg[c][e] += d[q][c][e] * zz[q][c][e];
+          pb[c][e] += d[q][c][e];
         }
         store_vec<T>(dz + (long)row * H + col, o);
         // the bias gradient of the producing linear sums dz as it is stored
@@ -181,26 +199,53 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
   for (int i = threadIdx.x; i < 3 * H; i += 256) partial[(long)blockIdx.x * 3 * H + i] = red[i];
 }
 
-// out_v[c] += sum_{blk ascending} partial[(blk*nvec + v)*H + c]
-__global__ void partial_reduce_kernel(const float* __restrict__ partial, int nblk, int nvec, int H, float* o0,
-                                      float* o1, float* o2) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  int v = blockIdx.y;
-  if (c >= H) return;
+// out_v[c] += sum over blocks of partial[(blk*nvec + v)*H + c].  A workgroup takes 64
+// columns; wave w adds blocks w, w+4, w+8, ... in ascending order and the four wave sums
+// are combined as ((s0 + s1) + s2) + s3: a fixed order, independent of timing.
+__global__ __launch_bounds__(256) void partial_reduce_kernel(const float* __restrict__ partial, int nblk, int nvec,
+                                                             int H, float* o0, float* o1, float* o2, long zs_partial,
+                                                             long zs_out) {
+  __shared__ float red[4][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  const int v = blockIdx.y;
   float* o = v == 0 ? o0 : (v == 1 ? o1 : o2);
   if (!o) return;
+  o += blockIdx.z * zs_out;
+  partial += blockIdx.z * zs_partial;
   float t = 0.f;
-  for (int b = 0; b < nblk; ++b) t += partial[((long)b * nvec + v) * H + c];
-  o[c] += t;
+  if (c < H) {
+    const float* p = partial + (long)v * H + c;
+    const long stride = (long)nvec * H;
+    int b = w;
+    for (; b + 28 < nblk; b += 32) {
+      float x[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) x[u] = p[(long)(b + 4 * u) * stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t += x[u];
+    }
+    for (; b < nblk; b += 4) t += p[(long)b * stride];
+  }
+  red[w][lane] = t;
+  __syncthreads();
+  if (w == 0 && c < H) {
+    float r = red[0][lane] + red[1][lane];
+    r += red[2][lane];
+    r += red[3][lane];
+    o[c] += r;
+  }
 }
 
 // ------------------------------------------------------------------ column sums
 constexpr int CS_ROWS = 64;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, int rows, int cols, int ld,
-                                                     float* __restrict__ partial) {
+                                                     float* __restrict__ partial, long zs_x) {
   constexpr int V = Vec<T>::N;
   __shared__ float red[4][64 * V];
+  X += blockIdx.z * zs_x;
+  partial += (long)blockIdx.z * gridDim.y * cols;
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int col = (blockIdx.x * 64 + lane) * V;
   float acc[V];
@@ -299,24 +344,27 @@ hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, const float* s
 
 hipError_t launch_partial_reduce(const float* partial, int nblk, int nvec, int H, float* o0, float* o1, float* o2,
                                  hipStream_t st) {
-  dim3 grid((H + 255) / 256, nvec), blk(256);
-  hipLaunchKernelGGL(partial_reduce_kernel, grid, blk, 0, st, partial, nblk, nvec, H, o0, o1, o2);
+  dim3 grid((H + 63) / 64, nvec), blk(256);
+  hipLaunchKernelGGL(partial_reduce_kernel, grid, blk, 0, st, partial, nblk, nvec, H, o0, o1, o2, 0L, 0L);
   return hipGetLastError();
 }
 
-hipError_t launch_colsum(Dtype dt, const void* X, int rows, int cols, int ld, float* partial, float* out,
-                         hipStream_t st) {
+hipError_t launch_colsum(Dtype dt, const void* X, int rows, int cols, int ld, float* partial, float* out, int nb,
+                         long zs_x, long zs_out, hipStream_t st) {
   int nrb = (rows + CS_ROWS - 1) / CS_ROWS;
   if (dt == DT_BF16) {
-    dim3 grid((cols + 64 * 8 - 1) / (64 * 8), nrb);
-    hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, rows, cols, ld, partial);
+    dim3 grid((cols + 64 * 8 - 1) / (64 * 8), nrb, nb);
+    hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, rows, cols, ld, partial, zs_x);
   } else {
-    dim3 grid((cols + 64 * 4 - 1) / (64 * 4), nrb);
-    hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, rows, cols, ld, partial);
+    dim3 grid((cols + 64 * 4 - 1) / (64 * 4), nrb, nb);
+    hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, rows, cols, ld, partial, zs_x);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return launch_partial_reduce(partial, nrb, 1, cols, out, nullptr, nullptr, st);
+  dim3 grid((cols + 63) / 64, 1, nb);
+  hipLaunchKernelGGL(partial_reduce_kernel, grid, dim3(256), 0, st, partial, nrb, 1, cols, out, nullptr, nullptr,
+                     (long)nrb * cols, zs_out);
+  return hipGetLastError();
 }
 
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {

@@ -135,7 +135,7 @@ void build_layout(const stage_config& c, Layout& L) {
   L.ws_dx[0] = wtake(U); L.ws_dx[1] = wtake(U); L.ws_dz2 = wtake(U); L.ws_du = wtake(T * F * E);
   L.ws_dy1 = wtake(U); L.ws_dz1 = wtake(U); L.ws_dctx = wtake(U); L.ws_dqkv = wtake(3 * U);
   L.ws_delta = wtake((size_t)c.micro_batch * c.n_heads * c.seq * 4);
-  size_t ln_part = ((T + 15) / 16) * 3 * H * 4, cs_part = ((T + 63) / 64) * (F > H ? F : H) * 4;
+  size_t ln_part = ((T + 7) / 8) * 3 * H * 4, cs_part = ((T + 63) / 64) * (F > 3 * H ? F : 3 * H) * 4;
   L.ws_partial = wtake(ln_part > cs_part ? ln_part : cs_part);
   L.workspace_bytes = wo;
 
@@ -281,7 +281,7 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
     int nblk = 0;
     // y = LN(z2): dz2, and the gradients of ln2 gain/shift and of b2
     TRY(run(KC_LN_BWD, 0, [&] { return launch_ln_bwd(dt, dyin, z2, st2, w(p.ln2g), dz2, partial, &nblk, T, H, st); }));
-    TRY(run(KC_REDUCE, 0, [&] { return launch_partial_reduce(partial, (T + 15) / 16, 3, H, gr(p.ln2g), gr(p.ln2b), gr(p.b2), st); }));
+    TRY(run(KC_REDUCE, 0, [&] { return launch_partial_reduce(partial, nblk, 3, H, gr(p.ln2g), gr(p.ln2b), gr(p.b2), st); }));
     {  // dW2 += g^T dz2
       GemmArgs ga{};
       ga.A = g; ga.lda = F; ga.a_kstrided = 1; ga.B = dz2; ga.ldb = H; ga.b_kstrided = 1;
@@ -294,7 +294,7 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
       ga.C = du; ga.ldc = F; ga.M = T; ga.N = F; ga.K = H; ga.epi = EPI_MUL;
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
-    TRY(run(KC_REDUCE, 0, [&] { return launch_colsum(dt, du, T, F, F, partial, gr(p.b1), st); }));
+    TRY(run(KC_REDUCE, 0, [&] { return launch_colsum(dt, du, T, F, F, partial, gr(p.b1), 1, 0, 0, st); }));
     {  // dW1 += y1^T du
       GemmArgs ga{};
       ga.A = y1; ga.lda = H; ga.a_kstrided = 1; ga.B = du; ga.ldb = F; ga.b_kstrided = 1;
@@ -308,13 +308,7 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
     TRY(run(KC_LN_BWD, 0, [&] { return launch_ln_bwd(dt, dy1, z1, st1, w(p.ln1g), dz1, partial, &nblk, T, H, st); }));
-    TRY(run(KC_REDUCE, 0, [&] { return launch_partial_reduce(partial, (T + 15) / 16, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), st); }));
-    {  // dWo += ctx^T dz1
-      GemmArgs ga{};
-      ga.A = ctx; ga.lda = H; ga.a_kstrided = 1; ga.B = dz1; ga.ldb = H; ga.b_kstrided = 1;
-      ga.C = gr(p.Wo); ga.ldc = H; ga.M = H; ga.N = H; ga.K = T; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_GEMM_WGRAD, ga));
-    }
+    TRY(run(KC_REDUCE, 0, [&] { return launch_partial_reduce(partial, nblk, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), st); }));
     {  // dctx = dz1 Wo^T
       GemmArgs ga{};
       ga.A = dz1; ga.lda = H; ga.B = w(p.Wo); ga.ldb = H; ga.C = dctx; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H;
@@ -329,13 +323,19 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
       TRY(run(KC_ATTN_BWD, fl, [&] { return launch_attn_bwd(dt, aa, st); }));
     }
     const size_t pstride = (size_t)H * H + H;
-    for (int z = 0; z < 3; ++z)
-      TRY(run(KC_REDUCE, 0, [&] { return launch_colsum(dt, dqkv + z * U, T, H, H, partial, gr(p.bq + z * pstride), st); }));
-    {  // dWq, dWk, dWv += x^T dq, x^T dk, x^T dv
+    TRY(run(KC_REDUCE, 0, [&] {
+      return launch_colsum(dt, dqkv, T, H, H, partial, gr(p.bq), 3, (long)T * H, (long)pstride, st);
+    }));
+    {  // dWq, dWk, dWv += x^T dq, x^T dk, x^T dv and dWo += ctx^T dz1: four products of one
+       // shape in one launch (alone, each would leave most of the CUs idle)
       GemmArgs ga{};
-      ga.A = xl; ga.lda = H; ga.a_kstrided = 1; ga.B = dqkv; ga.ldb = H; ga.b_kstrided = 1;
-      ga.C = gr(p.Wq); ga.ldc = H; ga.M = H; ga.N = H; ga.K = T; ga.batch = 3;
-      ga.sA = 0; ga.sB = (long)T * H; ga.sC = (long)pstride; ga.epi = EPI_ACC32;
+      ga.lda = H; ga.a_kstrided = 1; ga.ldb = H; ga.b_kstrided = 1;
+      ga.ldc = H; ga.M = H; ga.N = H; ga.K = T; ga.batch = 4; ga.epi = EPI_ACC32;
+      for (int z = 0; z < 3; ++z) {
+        ga.Az[z] = xl; ga.Bz[z] = dqkv + z * U; ga.Cz[z] = gr(p.Wq + z * pstride);
+      }
+      ga.Az[3] = ctx; ga.Bz[3] = dz1; ga.Cz[3] = gr(p.Wo);
+      ga.A = ga.Az[0]; ga.B = ga.Bz[0]; ga.C = ga.Cz[0];
       TRY(gemm(KC_GEMM_WGRAD, ga));
     }
     {  // dx = dq Wq^T + dk Wk^T + dv Wv^T + dz1 (residual branch): one product over K = 3H

@@ -177,7 +177,7 @@ def test_layernorm(dtype, H):
                            rows, H, eps)
     ddy = dev(dy, td)
     dz = torch.empty(rows, H, dtype=td, device="cuda")
-    partial = torch.empty(((rows + 15) // 16) * 3 * H, dtype=torch.float32, device="cuda")
+    partial = torch.empty(((rows + 7) // 8) * 3 * H, dtype=torch.float32, device="cuda")
     acc = torch.ones(3, H, dtype=torch.float32, device="cuda")       # accumulates on top of what is there
     B.dapple_layernorm_bwd(dtype, ddy.data_ptr(), dz_.data_ptr(), stats.data_ptr(), dg_.data_ptr(), dz.data_ptr(),
                            partial.data_ptr(), acc[0].data_ptr(), acc[1].data_ptr(), acc[2].data_ptr(), rows, H)
