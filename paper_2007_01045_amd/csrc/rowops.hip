@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
                                                      const float* __restrict__ stats, const T* __restrict__ gamma,
                                                      T* __restrict__ dz, float* __restrict__ partial, int rows, int H) {
   constexpr int V = Vec<T>::N;
-  extern __shared__ float red[];  // [3][H]
+  extern __shared__ __attribute__((aligned(16))) float red[];  // [4 waves][3][H]
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float pg[NCH][V], pb[NCH][V], pz[NCH][V], g[NCH][V];
 #pragma unroll
@@ -172,31 +172,31 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
       }
     }
   }
-  // combine the four waves in wave order: ((w0 + w1) + w2) + w3
-  for (int w = 0; w < 4; ++w) {
-    if (wave == w) {
+  // combine the four waves in wave order, ((w0 + w1) + w2) + w3, with 16-byte LDS accesses
+  float* mine = red + wave * 3 * H;
 #pragma unroll
-      for (int c = 0; c < NCH; ++c) {
-        int col = (c * 64 + lane) * V;
-        if (col < H) {
+  for (int c = 0; c < NCH; ++c) {
+    int col = (c * 64 + lane) * V;
+    if (col < H) {
 #pragma unroll
-          for (int e = 0; e < V; ++e) {
-            if (w == 0) {
-              red[0 * H + col + e] = pg[c][e];
-              red[1 * H + col + e] = pb[c][e];
-              red[2 * H + col + e] = pz[c][e];
-            } else {
-              red[0 * H + col + e] += pg[c][e];
-              red[1 * H + col + e] += pb[c][e];
-              red[2 * H + col + e] += pz[c][e];
-            }
-          }
-        }
+      for (int e = 0; e < V; e += 4) {
+        *(float4*)(mine + 0 * H + col + e) = make_float4(pg[c][e], pg[c][e + 1], pg[c][e + 2], pg[c][e + 3]);
+        *(float4*)(mine + 1 * H + col + e) = make_float4(pb[c][e], pb[c][e + 1], pb[c][e + 2], pb[c][e + 3]);
+        *(float4*)(mine + 2 * H + col + e) = make_float4(pz[c][e], pz[c][e + 1], pz[c][e + 2], pz[c][e + 3]);
       }
     }
-    __syncthreads();
   }
-  for (int i = threadIdx.x; i < 3 * H; i += 256) partial[(long)blockIdx.x * 3 * H + i] = red[i];
+  __syncthreads();
+  for (int i = threadIdx.x * 4; i < 3 * H; i += 256 * 4) {
+    float4 a = *(const float4*)(red + i), b = *(const float4*)(red + 3 * H + i);
+    float4 c2 = *(const float4*)(red + 6 * H + i), d2 = *(const float4*)(red + 9 * H + i);
+    float4 r;
+    r.x = ((a.x + b.x) + c2.x) + d2.x;
+    r.y = ((a.y + b.y) + c2.y) + d2.y;
+    r.z = ((a.z + b.z) + c2.z) + d2.z;
+    r.w = ((a.w + b.w) + c2.w) + d2.w;
+    *(float4*)(partial + (long)blockIdx.x * 3 * H + i) = r;
+  }
 }
 
 // out_v[c] += sum over blocks of partial[(blk*nvec + v)*H + c].  A workgroup takes 64
@@ -317,21 +317,30 @@ hipError_t launch_ln_fwd(Dtype dt, const void* z, const void* gamma, const void*
                        : ln_fwd_t<float>(z, gamma, beta, y, stats, rows, H, eps, st);
 }
 
+template <typename T, int N>
+static hipError_t ln_bwd_launch(const void* dy, const void* z, const float* stats, const void* g, void* dz,
+                                float* partial, int nb, int rows, int H, hipStream_t st) {
+  static bool attr = false;
+  if (!attr) {  // up to 96 KiB of LDS for the widest rows
+    hipError_t e = hipFuncSetAttribute((const void*)ln_bwd_kernel<T, N>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       12 * 64 * Vec<T>::N * N * 4);
+    if (e != hipSuccess) return e;
+    attr = true;
+  }
+  size_t sh = (size_t)12 * H * sizeof(float);
+  hipLaunchKernelGGL((ln_bwd_kernel<T, N>), dim3(nb), dim3(256), sh, st, (const T*)dy, (const T*)z, stats,
+                     (const T*)g, (T*)dz, partial, rows, H);
+  return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t ln_bwd_t(const void* dy, const void* z, const float* stats, const void* g, void* dz,
                            float* partial, int nb, int rows, int H, hipStream_t st) {
-  dim3 grid(nb), blk(256);
-  size_t sh = (size_t)3 * H * sizeof(float);
   int n = nch_for<T>(H);
-#define LNB(N)                                                                                                 \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, N>), grid, blk, sh, st, (const T*)dy, (const T*)z, stats, (const T*)g, \
-                     (T*)dz, partial, rows, H)
-  if (n <= 1) LNB(1);
-  else if (n <= 2) LNB(2);
-  else if (n <= 4) LNB(4);
-  else return hipErrorInvalidValue;
-#undef LNB
-  return hipGetLastError();
+  if (n <= 1) return ln_bwd_launch<T, 1>(dy, z, stats, g, dz, partial, nb, rows, H, st);
+  if (n <= 2) return ln_bwd_launch<T, 2>(dy, z, stats, g, dz, partial, nb, rows, H, st);
+  if (n <= 4) return ln_bwd_launch<T, 4>(dy, z, stats, g, dz, partial, nb, rows, H, st);
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, const float* stats, const void* gamma, void* dz,

@@ -63,8 +63,10 @@ struct Layout {
   size_t slot_head = 0;
   size_t slot_bytes = 0;
   // workspace (bytes)
-  size_t ws_dx[2] = {0, 0}, ws_dz2 = 0, ws_du = 0, ws_dy1 = 0, ws_dz1 = 0, ws_dctx = 0, ws_dqkv = 0, ws_delta = 0,
-         ws_partial = 0, ws_head = 0;
+  // buffers the side stream reads exist twice (layers alternate between the sets)
+  size_t ws_dx[2] = {0, 0}, ws_dz2[2] = {0, 0}, ws_du[2] = {0, 0}, ws_dy1 = 0, ws_dz1[2] = {0, 0}, ws_dctx = 0,
+         ws_dqkv[2] = {0, 0}, ws_delta = 0, ws_part_ln2[2] = {0, 0}, ws_part_ln1[2] = {0, 0}, ws_part_du[2] = {0, 0},
+         ws_part_qkv[2] = {0, 0}, ws_head = 0;
   size_t workspace_bytes = 0;
   // arena
   size_t grad_bytes = 0, arena_grads = 0, arena_slots = 0, arena_ws = 0, arena_bytes = 0;
@@ -132,11 +134,14 @@ void build_layout(const stage_config& c, Layout& L) {
 
   size_t wo = 0;
   auto wtake = [&](size_t bytes) { size_t o = wo; wo += align_up(bytes); return o; };
-  L.ws_dx[0] = wtake(U); L.ws_dx[1] = wtake(U); L.ws_dz2 = wtake(U); L.ws_du = wtake(T * F * E);
-  L.ws_dy1 = wtake(U); L.ws_dz1 = wtake(U); L.ws_dctx = wtake(U); L.ws_dqkv = wtake(3 * U);
+  L.ws_dx[0] = wtake(U); L.ws_dx[1] = wtake(U); L.ws_dy1 = wtake(U); L.ws_dctx = wtake(U);
   L.ws_delta = wtake((size_t)c.micro_batch * c.n_heads * c.seq * 4);
-  size_t ln_part = ((T + 7) / 8) * 3 * H * 4, cs_part = ((T + 63) / 64) * (F > 3 * H ? F : 3 * H) * 4;
-  L.ws_partial = wtake(ln_part > cs_part ? ln_part : cs_part);
+  const size_t ln_part = ((T + 7) / 8) * 3 * H * 4, cs_rows = (T + 63) / 64;
+  for (int p = 0; p < 2; ++p) {
+    L.ws_dz2[p] = wtake(U); L.ws_du[p] = wtake(T * F * E); L.ws_dz1[p] = wtake(U); L.ws_dqkv[p] = wtake(3 * U);
+    L.ws_part_ln2[p] = wtake(ln_part); L.ws_part_ln1[p] = wtake(ln_part);
+    L.ws_part_du[p] = wtake(cs_rows * F * 4); L.ws_part_qkv[p] = wtake(cs_rows * 3 * H * 4);
+  }
   L.workspace_bytes = wo;
 
   L.grad_bytes = align_up(L.n_params * 4);
@@ -158,7 +163,9 @@ struct dapple_stage {
   const char* W;   // parameters (device, caller-owned)
   char* arena;
   float* grads;
-  hipStream_t st;
+  hipStream_t st;         // the caller's stream: the critical path (forward; backward data gradients)
+  hipStream_t side = nullptr;  // library-owned: weight / bias / LayerNorm gradient work of a backward task
+  std::vector<hipEvent_t> ev;  // per layer: 4 "inputs ready" events (main -> side) + 1 "layer done" (side -> main)
   std::vector<int> slot_of_mb;   // slot -> micro-batch id, -1 = free
   int live = 0, peak_live = 0;
   uint64_t fwd_tasks = 0, bwd_tasks = 0, launches = 0;
@@ -174,7 +181,30 @@ struct dapple_stage {
 
   // run one launcher; with profiling on, bracket it with two events
   template <typename Fn>
-  int run(int cls, double flops, Fn&& fn) {
+  int run(int cls, double flops, Fn&& fn) { return run_on(st, cls, flops, fn); }
+
+  // main -> side: the side stream may start once the main stream has passed this point
+  int fork(int layer, int which) {
+    if (dry) return STAGE_OK;
+    hipEvent_t e = ev[layer * 5 + which];
+    if (hipEventRecord(e, st) != hipSuccess || hipStreamWaitEvent(side, e, 0) != hipSuccess)
+      return fail(STAGE_E_DEVICE, "event record / wait failed");
+    return STAGE_OK;
+  }
+  // side -> main, in two halves: mark the side work of a layer done; later make main wait for it
+  int side_done(int layer) {
+    if (dry) return STAGE_OK;
+    if (hipEventRecord(ev[layer * 5 + 4], side) != hipSuccess) return fail(STAGE_E_DEVICE, "event record failed");
+    return STAGE_OK;
+  }
+  int join(int layer) {
+    if (dry) return STAGE_OK;
+    if (hipStreamWaitEvent(st, ev[layer * 5 + 4], 0) != hipSuccess) return fail(STAGE_E_DEVICE, "event wait failed");
+    return STAGE_OK;
+  }
+
+  template <typename Fn>
+  int run_on(hipStream_t stream, int cls, double flops, Fn&& fn) {
     if (dry) { ++launches; return STAGE_OK; }
     ProfEvent* pe = nullptr;
     if (profiling) {
@@ -186,21 +216,21 @@ struct dapple_stage {
       }
       pe = &events[events_used++];
       pe->cls = cls; pe->flops = flops;
-      (void)hipEventRecord(pe->a, st);
+      (void)hipEventRecord(pe->a, stream);
     }
-    hipError_t e = fn();
-    if (pe) (void)hipEventRecord(pe->b, st);
+    hipError_t e = fn(stream);
+    if (pe) (void)hipEventRecord(pe->b, stream);
     ++launches;
     if (e != hipSuccess) return fail(STAGE_E_DEVICE, "kernel launch failed: %s", hipGetErrorString(e));
     return STAGE_OK;
   }
 
-  int gemm(int cls, GemmArgs g) {
+  int gemm(int cls, GemmArgs g, hipStream_t stream = nullptr, bool on_side = false) {
     if (g.kseg_len == 0) g.kseg_len = g.K;
     if (g.k_valid == 0) g.k_valid = g.K;
     if (g.batch == 0) g.batch = 1;
     double flops = 2.0 * g.M * g.N * (double)g.K * g.batch;
-    return run(cls, flops, [&] { return launch_gemm(dt, g, st); });
+    return run_on(on_side ? side : st, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); });
   }
 
   int forward(int s, const void* x, void* y, const void* aux);
@@ -215,7 +245,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
   char* sl = slot(s);
   (void)aux;
   const char* xin = sl + L.slot_x0;
-  TRY(run(KC_COPY, 0, [&] { return launch_copy(sl + L.slot_x0, x, U, st); }));
+  TRY(run(KC_COPY, 0, [&](hipStream_t q) { return launch_copy(sl + L.slot_x0, x, U, q); }));
   for (int l = 0; l < cfg.n_layers; ++l) {
     const LayerParams& p = L.lp[l];
     const LayerStash& a = L.ls[l];
@@ -235,7 +265,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
       aa.q = qkv; aa.k = qkv + U; aa.v = qkv + 2 * U; aa.ctx = ctx; aa.lse = lse;
       aa.b = cfg.micro_batch; aa.s = cfg.seq; aa.A = cfg.n_heads; aa.d = H / cfg.n_heads; aa.H = H;
       double fl = 4.0 * T * (double)cfg.seq * H;
-      TRY(run(KC_ATTN_FWD, fl, [&] { return launch_attn_fwd(dt, aa, st); }));
+      TRY(run(KC_ATTN_FWD, fl, [&](hipStream_t q) { return launch_attn_fwd(dt, aa, q); }));
     }
     {  // z1 = x + ctx Wo + bo
       GemmArgs ga{};
@@ -243,7 +273,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
       ga.aux = xin; ga.ldaux = H; ga.C = z1; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H; ga.epi = EPI_BIAS | EPI_ADD;
       TRY(gemm(KC_GEMM_FWD, ga));
     }
-    TRY(run(KC_LN_FWD, 0, [&] { return launch_ln_fwd(dt, z1, w(p.ln1g), w(p.ln1b), y1, st1, T, H, cfg.ln_eps, st); }));
+    TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) { return launch_ln_fwd(dt, z1, w(p.ln1g), w(p.ln1b), y1, st1, T, H, cfg.ln_eps, q); }));
     {  // g = GELU(y1 W1 + b1), gp = GELU'(y1 W1 + b1)
       GemmArgs ga{};
       ga.A = y1; ga.lda = H; ga.B = w(p.W1); ga.ldb = F; ga.b_kstrided = 1; ga.bias = w(p.b1);
@@ -256,37 +286,51 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
       ga.aux = y1; ga.ldaux = H; ga.C = z2; ga.ldc = H; ga.M = T; ga.N = H; ga.K = F; ga.epi = EPI_BIAS | EPI_ADD;
       TRY(gemm(KC_GEMM_FWD, ga));
     }
-    TRY(run(KC_LN_FWD, 0, [&] { return launch_ln_fwd(dt, z2, w(p.ln2g), w(p.ln2b), yout, st2, T, H, cfg.ln_eps, st); }));
+    TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) { return launch_ln_fwd(dt, z2, w(p.ln2g), w(p.ln2b), yout, st2, T, H, cfg.ln_eps, q); }));
     xin = yout;
   }
   return STAGE_OK;
 }
 
 int dapple_stage::backward(int s, const void* dy, void* dx) {
+  // Two streams.  The caller's stream runs the chain that produces dx (LayerNorm backward,
+  // data-gradient products, attention backward): it is the critical path.  Everything that only
+  // feeds the gradient accumulators (weight-gradient products, bias column sums, LayerNorm
+  // parameter sums) goes to the side stream as soon as its inputs exist, so those kernels fill
+  // the CUs the small data-gradient products leave idle.  All accumulator updates happen on the
+  // side stream in program order: the result does not depend on how the two streams interleave.
   const int H = cfg.hidden, F = cfg.ffn, T = cfg.micro_batch * cfg.seq;
   const size_t U = (size_t)T * H * E();
   char* sl = slot(s);
-  char *dz2 = ws(L.ws_dz2), *du = ws(L.ws_du), *dy1 = ws(L.ws_dy1), *dz1 = ws(L.ws_dz1), *dctx = ws(L.ws_dctx),
-       *dqkv = ws(L.ws_dqkv);
-  float *delta = (float*)ws(L.ws_delta), *partial = (float*)ws(L.ws_partial);
+  char *dy1 = ws(L.ws_dy1), *dctx = ws(L.ws_dctx);
+  float* delta = (float*)ws(L.ws_delta);
   const char* dyin = (const char*)dy;
   for (int l = cfg.n_layers - 1; l >= 0; --l) {
     const LayerParams& p = L.lp[l];
     const LayerStash& a = L.ls[l];
+    const int ps = l & 1;  // workspace set of this layer
+    char *dz2 = ws(L.ws_dz2[ps]), *du = ws(L.ws_du[ps]), *dz1 = ws(L.ws_dz1[ps]), *dqkv = ws(L.ws_dqkv[ps]);
+    float *part_ln2 = (float*)ws(L.ws_part_ln2[ps]), *part_ln1 = (float*)ws(L.ws_part_ln1[ps]),
+          *part_du = (float*)ws(L.ws_part_du[ps]), *part_qkv = (float*)ws(L.ws_part_qkv[ps]);
     const char* xl = l == 0 ? sl + L.slot_x0 : sl + L.ls[l - 1].y;
     char *qkv = sl + a.qkv, *ctx = sl + a.ctx, *z1 = sl + a.z1, *y1 = sl + a.y1, *gp = sl + a.gp, *g = sl + a.g,
          *z2 = sl + a.z2;
     float *lse = (float*)(sl + a.lse), *st1 = (float*)(sl + a.st1), *st2 = (float*)(sl + a.st2);
     char* dxout = l == 0 ? (char*)dx : ws(L.ws_dx[l & 1]);
+    const size_t pstride = (size_t)H * H + H;
     int nblk = 0;
-    // y = LN(z2): dz2, and the gradients of ln2 gain/shift and of b2
-    TRY(run(KC_LN_BWD, 0, [&] { return launch_ln_bwd(dt, dyin, z2, st2, w(p.ln2g), dz2, partial, &nblk, T, H, st); }));
-    TRY(run(KC_REDUCE, 0, [&] { return launch_partial_reduce(partial, nblk, 3, H, gr(p.ln2g), gr(p.ln2b), gr(p.b2), st); }));
+    // this layer's workspace set was last read by the side work of layer l + 2
+    if (l + 2 < cfg.n_layers) TRY(join(l + 2));
+
+    // y = LN(z2): dz2, and block partial sums for the gradients of ln2 gain/shift and of b2
+    TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dyin, z2, st2, w(p.ln2g), dz2, part_ln2, &nblk, T, H, q); }));
+    TRY(fork(l, 0));
+    TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln2, nblk, 3, H, gr(p.ln2g), gr(p.ln2b), gr(p.b2), q); }));
     {  // dW2 += g^T dz2
       GemmArgs ga{};
       ga.A = g; ga.lda = F; ga.a_kstrided = 1; ga.B = dz2; ga.ldb = H; ga.b_kstrided = 1;
       ga.C = gr(p.W2); ga.ldc = H; ga.M = F; ga.N = H; ga.K = T; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_GEMM_WGRAD, ga));
+      TRY(gemm(KC_GEMM_WGRAD, ga, nullptr, true));
     }
     {  // du = (dz2 W2^T) o GELU'(u)
       GemmArgs ga{};
@@ -294,12 +338,13 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
       ga.C = du; ga.ldc = F; ga.M = T; ga.N = F; ga.K = H; ga.epi = EPI_MUL;
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
-    TRY(run(KC_REDUCE, 0, [&] { return launch_colsum(dt, du, T, F, F, partial, gr(p.b1), 1, 0, 0, st); }));
+    TRY(fork(l, 1));
+    TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_colsum(dt, du, T, F, F, part_du, gr(p.b1), 1, 0, 0, q); }));
     {  // dW1 += y1^T du
       GemmArgs ga{};
       ga.A = y1; ga.lda = H; ga.a_kstrided = 1; ga.B = du; ga.ldb = F; ga.b_kstrided = 1;
       ga.C = gr(p.W1); ga.ldc = F; ga.M = H; ga.N = F; ga.K = T; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_GEMM_WGRAD, ga));
+      TRY(gemm(KC_GEMM_WGRAD, ga, nullptr, true));
     }
     {  // dy1 = du W1^T + dz2 (residual branch)
       GemmArgs ga{};
@@ -307,8 +352,9 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
       ga.C = dy1; ga.ldc = H; ga.M = T; ga.N = H; ga.K = F; ga.epi = EPI_ADD;
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
-    TRY(run(KC_LN_BWD, 0, [&] { return launch_ln_bwd(dt, dy1, z1, st1, w(p.ln1g), dz1, partial, &nblk, T, H, st); }));
-    TRY(run(KC_REDUCE, 0, [&] { return launch_partial_reduce(partial, nblk, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), st); }));
+    TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dy1, z1, st1, w(p.ln1g), dz1, part_ln1, &nblk, T, H, q); }));
+    TRY(fork(l, 2));
+    TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln1, nblk, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), q); }));
     {  // dctx = dz1 Wo^T
       GemmArgs ga{};
       ga.A = dz1; ga.lda = H; ga.B = w(p.Wo); ga.ldb = H; ga.C = dctx; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H;
@@ -320,11 +366,11 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
       aa.dq = dqkv; aa.dk = dqkv + U; aa.dv = dqkv + 2 * U; aa.delta = delta;
       aa.b = cfg.micro_batch; aa.s = cfg.seq; aa.A = cfg.n_heads; aa.d = H / cfg.n_heads; aa.H = H;
       double fl = 8.0 * T * (double)cfg.seq * H;
-      TRY(run(KC_ATTN_BWD, fl, [&] { return launch_attn_bwd(dt, aa, st); }));
+      TRY(run(KC_ATTN_BWD, fl, [&](hipStream_t q) { return launch_attn_bwd(dt, aa, q); }));
     }
-    const size_t pstride = (size_t)H * H + H;
-    TRY(run(KC_REDUCE, 0, [&] {
-      return launch_colsum(dt, dqkv, T, H, H, partial, gr(p.bq), 3, (long)T * H, (long)pstride, st);
+    TRY(fork(l, 3));
+    TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) {
+      return launch_colsum(dt, dqkv, T, H, H, part_qkv, gr(p.bq), 3, (long)T * H, (long)pstride, q);
     }));
     {  // dWq, dWk, dWv += x^T dq, x^T dk, x^T dv and dWo += ctx^T dz1: four products of one
        // shape in one launch (alone, each would leave most of the CUs idle)
@@ -336,8 +382,9 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
       }
       ga.Az[3] = ctx; ga.Bz[3] = dz1; ga.Cz[3] = gr(p.Wo);
       ga.A = ga.Az[0]; ga.B = ga.Bz[0]; ga.C = ga.Cz[0];
-      TRY(gemm(KC_GEMM_WGRAD, ga));
+      TRY(gemm(KC_GEMM_WGRAD, ga, nullptr, true));
     }
+    TRY(side_done(l));
     {  // dx = dq Wq^T + dk Wk^T + dv Wv^T + dz1 (residual branch): one product over K = 3H
       GemmArgs ga{};
       ga.A = dqkv; ga.lda = H; ga.B = w(p.Wq); ga.ldb = H; ga.aux = dz1; ga.ldaux = H;
@@ -347,6 +394,10 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
     }
     dyin = dxout;
   }
+  // The task ends when both streams are done: whatever follows on the caller's stream (the next
+  // forward reusing this slot, a gradient read-out) is ordered after the accumulator updates.
+  TRY(join(0));
+  if (cfg.n_layers > 1) TRY(join(1));
   return STAGE_OK;
 }
 
@@ -440,7 +491,20 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
   h->grads = (float*)arena_dev;
   h->st = (hipStream_t)hip_stream;
   h->slot_of_mb.assign(cfg->max_slots, -1);
-  int rc = h->run(KC_COPY, 0, [&] { return launch_zero(h->grads, h->L.grad_bytes, h->st); });
+  if (!dry) {
+    // default priority on purpose; the side stream never outlives the handle
+    if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) {
+      delete h;
+      return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
+    }
+    h->ev.resize((size_t)cfg->n_layers * 5);
+    for (auto& e : h->ev)
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+        delete h;
+        return fail(STAGE_E_DEVICE, "hipEventCreate failed");
+      }
+  }
+  int rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->grads, h->L.grad_bytes, q); });
   if (rc != STAGE_OK) { delete h; return rc; }
   *out = h;
   return STAGE_OK;
@@ -448,8 +512,13 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
 
 int stage_destroy(stage_handle h) {
   if (!h) return fail(STAGE_E_NULL, "handle is NULL");
-  if (!h->dry) (void)hipStreamSynchronize(h->st);
+  if (!h->dry) {
+    (void)hipStreamSynchronize(h->st);
+    if (h->side) (void)hipStreamSynchronize(h->side);
+  }
   for (auto& e : h->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  for (auto& e : h->ev) (void)hipEventDestroy(e);
+  if (h->side) (void)hipStreamDestroy(h->side);
   delete h;
   return STAGE_OK;
 }
@@ -542,7 +611,7 @@ int stage_grads(stage_handle h, void** grads_dev, uint64_t* n) {
 
 int stage_zero_grads(stage_handle h) {
   if (!h) return fail(STAGE_E_NULL, "handle is NULL");
-  return h->run(KC_COPY, 0, [&] { return launch_zero(h->grads, h->L.grad_bytes, h->st); });
+  return h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->grads, h->L.grad_bytes, q); });
 }
 
 int stage_stats(stage_handle h, stage_stats_t* out) {
@@ -566,7 +635,8 @@ int stage_reset_stats(stage_handle h) {
 
 int stage_profile_enable(stage_handle h, int on) {
   if (!h) return fail(STAGE_E_NULL, "handle is NULL");
-  if (!h->dry && hipStreamSynchronize(h->st) != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed");
+  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess))
+    return fail(STAGE_E_DEVICE, "stream synchronise failed");
   h->profiling = on != 0;
   h->events_used = 0;
   return STAGE_OK;
@@ -574,7 +644,8 @@ int stage_profile_enable(stage_handle h, int on) {
 
 int stage_profile_read(stage_handle h, int n, uint64_t* launches, double* ms, double* flops) {
   if (!h || !launches || !ms || !flops) return fail(STAGE_E_NULL, "arguments must not be NULL");
-  if (!h->dry && hipStreamSynchronize(h->st) != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed");
+  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess))
+    return fail(STAGE_E_DEVICE, "stream synchronise failed");
   for (int i = 0; i < n; ++i) { launches[i] = 0; ms[i] = 0; flops[i] = 0; }
   for (size_t i = 0; i < h->events_used; ++i) {
     const ProfEvent& e = h->events[i];
@@ -593,6 +664,7 @@ int stage_sync(stage_handle h) {
   if (!h) return fail(STAGE_E_NULL, "handle is NULL");
   if (h->dry) return STAGE_OK;
   hipError_t e = hipStreamSynchronize(h->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(h->side);
   if (e != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed: %s", hipGetErrorString(e));
   return STAGE_OK;
 }
