@@ -28,9 +28,12 @@
  *     pointer is HOST memory.  The library allocates no device memory: it
  *     sub-allocates the arena handed to stage_init (gradient accumulators,
  *     max_slots activation slots, workspace).
- *   - all device work is enqueued on the HIP stream given to stage_init; no call
- *     synchronises the stream except stage_sync.  Buffers passed to a call must stay
- *     valid until the stream has passed that call.
+ *   - all device work is ordered in the HIP stream given to stage_init; no call
+ *     synchronises the stream except stage_sync.  (A backward task also uses a second,
+ *     library-owned stream for the gradient-accumulator kernels; it is forked from and
+ *     joined back into the caller's stream inside the task, so the caller's stream order
+ *     still covers everything.)  Buffers passed to a call must stay valid until the
+ *     stream has passed that call.
  *   - every call returns 0 on success or a negative STAGE_E_* code; nothing throws
  *     or aborts.  stage_last_error() gives a message for the last failure of the
  *     calling thread.  A failed call enqueues nothing and changes no state.
@@ -80,6 +83,9 @@ typedef struct {
   int32_t flags;         /* STAGE_FLAG_* */
   float ln_eps;          /* added to the biased variance inside the square root */
   float loss_scale;      /* MLM head: loss = loss_scale * sum over predicted rows */
+  int32_t mlm_max_rows;  /* MLM head: most predicted positions per micro-batch (0 = all b*s rows);
+                            sizes the head's buffers; more predicted rows than this are dropped and
+                            stage_sync then returns STAGE_E_CONFIG */
 } stage_config;
 
 typedef struct {

@@ -27,7 +27,7 @@ class stage_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "hidden", "n_heads", "ffn", "seq", "micro_batch", "max_slots", "dtype",
                  "has_embedding", "has_mlm_head", "vocab", "max_pos", "flags")] + \
-               [("ln_eps", C.c_float), ("loss_scale", C.c_float)]
+               [("ln_eps", C.c_float), ("loss_scale", C.c_float), ("mlm_max_rows", C.c_int32)]
 
 
 class stage_sizes(C.Structure):
@@ -115,9 +115,11 @@ def _check(rc):
 
 
 def make_config(n_layers, hidden, n_heads, ffn, seq, micro_batch, max_slots, dtype, has_embedding=0,
-                has_mlm_head=0, vocab=0, max_pos=0, flags=0, ln_eps=1e-12, loss_scale=1.0) -> stage_config:
+                has_mlm_head=0, vocab=0, max_pos=0, flags=0, ln_eps=1e-12, loss_scale=1.0,
+                mlm_max_rows=0) -> stage_config:
     return stage_config(n_layers, hidden, n_heads, ffn, seq, micro_batch, max_slots, dtype,
-                        int(has_embedding), int(has_mlm_head), vocab, max_pos, flags, ln_eps, loss_scale)
+                        int(has_embedding), int(has_mlm_head), vocab, max_pos, flags, ln_eps, loss_scale,
+                        mlm_max_rows)
 
 
 # ---- thin wrappers, one per C entry point ---------------------------------

@@ -36,6 +36,8 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs& g, long zc, long 
     ((T*)g.C2)[o] = from_f32<T>(b);
   } else if (g.epi & EPI_ACC32) {
     ((float*)g.C)[o] += t;
+  } else if (g.epi & EPI_OUT32) {
+    ((float*)g.C)[o] = t;
   } else {
     ((T*)g.C)[o] = from_f32<T>(t);
   }
@@ -61,8 +63,8 @@ __global__ void gemm_plain_kernel(GemmArgs g) {
     const T* Bs = B + s * g.segB;
     for (int k = 0; k < g.kseg_len; ++k) {
       if (k >= g.k_valid) break;
-      float a = to_f32(g.a_kstrided ? As[(long)k * g.lda + row] : As[(long)row * g.lda + k]);
-      float b = to_f32(g.b_kstrided ? Bs[(long)k * g.ldb + col] : Bs[(long)col * g.ldb + k]);
+      float a = row < g.m_valid ? to_f32(g.a_kstrided ? As[(long)k * g.lda + row] : As[(long)row * g.lda + k]) : 0.f;
+      float b = col < g.n_valid ? to_f32(g.b_kstrided ? Bs[(long)k * g.ldb + col] : Bs[(long)col * g.ldb + k]) : 0.f;
       acc = fmaf(a, b, acc);
     }
   }
@@ -216,8 +218,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   const int nk = g.K / BK;
   const int tiles_per_seg = g.kseg_len / BK;
   // bytes of one segment of each operand that may be read (beyond: zero)
-  const long a_ext = AKS ? ((long)(g.k_valid - 1) * g.lda + g.M) * 2 : ((long)(g.M - 1) * g.lda + g.kseg_len) * 2;
-  const long b_ext = BKS ? ((long)(g.k_valid - 1) * g.ldb + g.N) * 2 : ((long)(g.N - 1) * g.ldb + g.kseg_len) * 2;
+  const long a_ext =
+      AKS ? ((long)(g.k_valid - 1) * g.lda + g.m_valid) * 2 : ((long)(g.m_valid - 1) * g.lda + g.kseg_len) * 2;
+  const long b_ext =
+      BKS ? ((long)(g.k_valid - 1) * g.ldb + g.n_valid) * 2 : ((long)(g.n_valid - 1) * g.ldb + g.kseg_len) * 2;
 
   TA ta;
   TB tb;
@@ -360,7 +364,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
             }
           }
         }
-        if (epi & EPI_ACC32) {
+        if (epi & EPI_OUT32) {
+#pragma unroll
+          for (int u = 0; u < HB; ++u)
+            if (rows[u] < g.M && cols[u] < g.N) *(float4*)((float*)Cb + zc + (long)rows[u] * g.ldc + cols[u]) = t[u];
+        } else if (epi & EPI_ACC32) {
           float4 cv[HB];
 #pragma unroll
           for (int u = 0; u < HB; ++u) {
@@ -468,8 +476,6 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
           !aligned_to(g.Cz[z], 16))
         return false;
   }
-  if (g.a_kstrided && g.M % 8) return false;
-  if (g.b_kstrided && g.N % 8) return false;
   if ((g.epi & (EPI_ADD | EPI_MUL)) && (g.ldaux % 4 || !aligned_to(g.aux, 8))) return false;
   if ((g.epi & EPI_BIAS) && !aligned_to(g.bias, 8)) return false;
   if ((g.epi & EPI_GELU) && !aligned_to(g.C2, 8)) return false;

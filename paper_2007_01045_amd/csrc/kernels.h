@@ -21,7 +21,8 @@ enum GemmEpi {
   EPI_ADD = 2,    // t += aux[m,n]
   EPI_MUL = 4,    // t *= aux[m,n]
   EPI_GELU = 8,   // C = gelu(t), C2 = gelu'(t)
-  EPI_ACC32 = 16  // C is fp32 and C += t (weight-gradient accumulation)
+  EPI_ACC32 = 16,  // C is fp32 and C += t (weight-gradient accumulation)
+  EPI_OUT32 = 32   // C is fp32 and C = t
 };
 
 struct GemmArgs {
@@ -45,6 +46,7 @@ struct GemmArgs {
   const void* Bz[4];
   void* Cz[4];
   int k_valid;  // k-strided operands: rows k >= k_valid read as zero (K itself is padded)
+  int m_valid, n_valid;  // rows of A / B that exist in memory (0 = M / N); rows beyond read as zero
   int epi;
 };
 
@@ -92,11 +94,25 @@ hipError_t launch_zero(void* dst, size_t bytes, hipStream_t st);
 
 // ---------------------------------------------------------------- embedding / head
 // e[r] = E_w[ids[r]] + E_p[r % s]
-hipError_t launch_embed_gather(Dtype dt, const int32_t* ids, const void* Ew, const void* Ep, void* e,
-                               int rows, int s, int H, hipStream_t st);
+hipError_t launch_embed_gather(Dtype dt, const int32_t* ids, const void* Ew, const void* Ep, void* e, int rows, int s,
+                               int H, int vocab, hipStream_t st);
 // dEw[id] += sum over rows r with ids[r] == id (ascending r) of de[r];
-// dEp[p] += sum over sequences of de[bi*s + p]
-hipError_t launch_embed_bwd(Dtype dt, const int32_t* ids, const void* de, float* dEw, float* dEp,
-                            int rows, int s, int H, int vocab, int32_t* scratch, hipStream_t st);
+// dEp[p] += sum over the b sequences of de[bi*s + p]
+hipError_t launch_embed_bwd(Dtype dt, const int32_t* ids, const void* de, float* dEw, float* dEp, int b, int s, int H,
+                            int vocab, hipStream_t st);
+// rows_idx / tgt [np], np >= cap: the rows with target >= 0 in ascending order, at most cap of them
+// (-1 / 0 in every other entry); info[0] = count, info[1] set to 1 if more than cap rows are predicted
+hipError_t launch_mlm_compact(const int32_t* targets, int T, int cap, int np, int vocab, int32_t* rows_idx,
+                              int32_t* tgt, int32_t* info, hipStream_t st);
+// dst[i] = src[idx[i]] (zero row if idx[i] is outside [0, nsrc)); dst[idx[i]] = src[i]
+hipError_t launch_gather_rows(Dtype dt, const void* src, const int32_t* idx, void* dst, int n, int H, int nsrc,
+                              hipStream_t st);
+hipError_t launch_scatter_rows(Dtype dt, const void* src, const int32_t* idx, void* dst, int n, int H, int ndst,
+                               hipStream_t st);
+// logits fp32 [n, VP] (+ bias over v < V) -> dz [n, VP], row_loss [n], loss_out[0] = loss_scale * sum(row_loss)
+hipError_t launch_mlm_ce(Dtype dt, const float* logits, const void* bias, const int32_t* rows_idx, const int32_t* tgt,
+                         int n, int V, int VP, float loss_scale, void* dz, float* row_loss, float* loss_out,
+                         hipStream_t st);
+hipError_t launch_mul(Dtype dt, const void* a, const void* b, void* c, long n, hipStream_t st);
 
 }  // namespace dapple

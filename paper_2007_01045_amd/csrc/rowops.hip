@@ -204,7 +204,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
 // are combined as ((s0 + s1) + s2) + s3: a fixed order, independent of timing.
 __global__ __launch_bounds__(256) void partial_reduce_kernel(const float* __restrict__ partial, int nblk, int nvec,
                                                              int H, float* o0, float* o1, float* o2, long zs_partial,
-                                                             long zs_out) {
+                                                             long zs_out, int PS) {
   __shared__ float red[4][64];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + lane;
@@ -215,8 +215,8 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const float* __rest
   partial += blockIdx.z * zs_partial;
   float t = 0.f;
   if (c < H) {
-    const float* p = partial + (long)v * H + c;
-    const long stride = (long)nvec * H;
+    const float* p = partial + (long)v * PS + c;  // PS: row stride of the partial blocks
+    const long stride = (long)nvec * PS;
     int b = w;
     for (; b + 28 < nblk; b += 32) {
       float x[8];
@@ -241,11 +241,11 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const float* __rest
 constexpr int CS_ROWS = 64;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, int rows, int cols, int ld,
-                                                     float* __restrict__ partial, long zs_x) {
+                                                     float* __restrict__ partial, long zs_x, int PS) {
   constexpr int V = Vec<T>::N;
   __shared__ float red[4][64 * V];
   X += blockIdx.z * zs_x;
-  partial += (long)blockIdx.z * gridDim.y * cols;
+  partial += (long)blockIdx.z * gridDim.y * PS;
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int col = (blockIdx.x * 64 + lane) * V;
   float acc[V];
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, in
       float t = red[0][lane * V + e] + red[1][lane * V + e];
       t += red[2][lane * V + e];
       t += red[3][lane * V + e];
-      partial[(long)blockIdx.y * cols + col + e] = t;
+      partial[(long)blockIdx.y * PS + col + e] = t;
     }
   }
 }
@@ -354,25 +354,27 @@ hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, const float* s
 hipError_t launch_partial_reduce(const float* partial, int nblk, int nvec, int H, float* o0, float* o1, float* o2,
                                  hipStream_t st) {
   dim3 grid((H + 63) / 64, nvec), blk(256);
-  hipLaunchKernelGGL(partial_reduce_kernel, grid, blk, 0, st, partial, nblk, nvec, H, o0, o1, o2, 0L, 0L);
+  hipLaunchKernelGGL(partial_reduce_kernel, grid, blk, 0, st, partial, nblk, nvec, H, o0, o1, o2, 0L, 0L, H);
   return hipGetLastError();
 }
 
 hipError_t launch_colsum(Dtype dt, const void* X, int rows, int cols, int ld, float* partial, float* out, int nb,
                          long zs_x, long zs_out, hipStream_t st) {
   int nrb = (rows + CS_ROWS - 1) / CS_ROWS;
+  int vec = dt == DT_BF16 ? 8 : 4;
+  int PS = (cols + vec - 1) / vec * vec;  // whole vectors: the last one may reach into X's row padding (ld >= PS)
   if (dt == DT_BF16) {
     dim3 grid((cols + 64 * 8 - 1) / (64 * 8), nrb, nb);
-    hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, rows, cols, ld, partial, zs_x);
+    hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, rows, cols, ld, partial, zs_x, PS);
   } else {
     dim3 grid((cols + 64 * 4 - 1) / (64 * 4), nrb, nb);
-    hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, rows, cols, ld, partial, zs_x);
+    hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, rows, cols, ld, partial, zs_x, PS);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   dim3 grid((cols + 63) / 64, 1, nb);
   hipLaunchKernelGGL(partial_reduce_kernel, grid, dim3(256), 0, st, partial, nrb, 1, cols, out, nullptr, nullptr,
-                     (long)nrb * cols, zs_out);
+                     (long)nrb * PS, zs_out, PS);
   return hipGetLastError();
 }
 

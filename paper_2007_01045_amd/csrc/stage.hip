@@ -60,7 +60,12 @@ struct Layout {
   // slot
   size_t slot_x0 = 0, slot_ids = 0, slot_embsum = 0, slot_embst = 0;
   std::vector<LayerStash> ls;
-  size_t slot_head = 0;
+  // masked-LM head: NP gathered rows (multiple of 64), VP padded vocabulary (multiple of 64)
+  int NP = 0, VP = 0;
+  size_t sh_rows = 0, sh_tgt = 0, sh_r = 0, sh_gl = 0, sh_glp = 0, sh_st = 0, sh_t = 0, sh_dz = 0;
+  size_t wh_logits = 0, wh_rowloss = 0, wh_dt = 0, wh_dgl = 0, wh_dh = 0, wh_dr = 0, wh_dyfull = 0, wh_part = 0,
+         wh_info = 0;
+  size_t we_dx0 = 0, we_de = 0, we_part = 0;
   size_t slot_bytes = 0;
   // workspace (bytes)
   // buffers the side stream reads exist twice (layers alternate between the sets)
@@ -130,6 +135,14 @@ void build_layout(const stage_config& c, Layout& L) {
     bool keep_y = l + 1 < c.n_layers || c.has_mlm_head;
     s.y = keep_y ? stake(U) : 0;
   }
+  if (c.has_mlm_head) {
+    int cap = c.mlm_max_rows > 0 && c.mlm_max_rows < (int)T ? c.mlm_max_rows : (int)T;
+    L.NP = (cap + 63) / 64 * 64;
+    L.VP = (c.vocab + 63) / 64 * 64;
+    const size_t NP = L.NP, VP = L.VP;
+    L.sh_rows = stake(NP * 4); L.sh_tgt = stake(NP * 4); L.sh_r = stake(NP * H * E); L.sh_gl = stake(NP * H * E);
+    L.sh_glp = stake(NP * H * E); L.sh_st = stake(2 * NP * 4); L.sh_t = stake(NP * H * E); L.sh_dz = stake(NP * VP * E);
+  }
   L.slot_bytes = so;
 
   size_t wo = 0;
@@ -141,6 +154,16 @@ void build_layout(const stage_config& c, Layout& L) {
     L.ws_dz2[p] = wtake(U); L.ws_du[p] = wtake(T * F * E); L.ws_dz1[p] = wtake(U); L.ws_dqkv[p] = wtake(3 * U);
     L.ws_part_ln2[p] = wtake(ln_part); L.ws_part_ln1[p] = wtake(ln_part);
     L.ws_part_du[p] = wtake(cs_rows * F * 4); L.ws_part_qkv[p] = wtake(cs_rows * 3 * H * 4);
+  }
+  if (c.has_mlm_head) {
+    const size_t NP = L.NP, VP = L.VP;
+    L.wh_logits = wtake(NP * VP * 4); L.wh_rowloss = wtake(NP * 4); L.wh_dt = wtake(NP * H * E);
+    L.wh_dgl = wtake(NP * H * E); L.wh_dh = wtake(NP * H * E); L.wh_dr = wtake(NP * H * E); L.wh_dyfull = wtake(U);
+    size_t lp = ((NP + 7) / 8) * 3 * H * 4, cp = ((NP + 63) / 64) * VP * 4;
+    L.wh_part = wtake(lp > cp ? lp : cp); L.wh_info = wtake(16);
+  }
+  if (c.has_embedding) {
+    L.we_dx0 = wtake(U); L.we_de = wtake(U); L.we_part = wtake(ln_part);
   }
   L.workspace_bytes = wo;
 
@@ -228,6 +251,8 @@ struct dapple_stage {
   int gemm(int cls, GemmArgs g, hipStream_t stream = nullptr, bool on_side = false) {
     if (g.kseg_len == 0) g.kseg_len = g.K;
     if (g.k_valid == 0) g.k_valid = g.K;
+    if (g.m_valid == 0) g.m_valid = g.M;
+    if (g.n_valid == 0) g.n_valid = g.N;
     if (g.batch == 0) g.batch = 1;
     double flops = 2.0 * g.M * g.N * (double)g.K * g.batch;
     return run_on(on_side ? side : st, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); });
@@ -245,7 +270,20 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
   char* sl = slot(s);
   (void)aux;
   const char* xin = sl + L.slot_x0;
-  TRY(run(KC_COPY, 0, [&](hipStream_t q) { return launch_copy(sl + L.slot_x0, x, U, q); }));
+  if (cfg.has_embedding) {
+    // x = LN(E_w[id] + E_p[pos]); the ids and the pre-LN sum are kept for the backward
+    int32_t* ids = (int32_t*)(sl + L.slot_ids);
+    char* esum = sl + L.slot_embsum;
+    TRY(run(KC_COPY, 0, [&](hipStream_t q) { return launch_copy(ids, x, (size_t)T * 4, q); }));
+    TRY(run(KC_EMBED, 0, [&](hipStream_t q) {
+      return launch_embed_gather(dt, ids, w(L.embEw), w(L.embEp), esum, T, cfg.seq, H, cfg.vocab, q);
+    }));
+    TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) {
+      return launch_ln_fwd(dt, esum, w(L.embG), w(L.embB), sl + L.slot_x0, (float*)(sl + L.slot_embst), T, H, cfg.ln_eps, q);
+    }));
+  } else {
+    TRY(run(KC_COPY, 0, [&](hipStream_t q) { return launch_copy(sl + L.slot_x0, x, U, q); }));
+  }
   for (int l = 0; l < cfg.n_layers; ++l) {
     const LayerParams& p = L.lp[l];
     const LayerStash& a = L.ls[l];
@@ -289,6 +327,33 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
     TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) { return launch_ln_fwd(dt, z2, w(p.ln2g), w(p.ln2b), yout, st2, T, H, cfg.ln_eps, q); }));
     xin = yout;
   }
+  if (cfg.has_mlm_head) {
+    // gather the predicted rows, t = LN(GELU(r Wt + bt)), z = t E_out^T (+ b_out inside the
+    // cross-entropy kernel), loss -> y[0]; dz is kept in the slot for the backward
+    const int NP = L.NP, VP = L.VP, V = cfg.vocab;
+    int32_t *rows_idx = (int32_t*)(sl + L.sh_rows), *tgt = (int32_t*)(sl + L.sh_tgt), *info = (int32_t*)ws(L.wh_info);
+    char *r = sl + L.sh_r, *gl = sl + L.sh_gl, *glp = sl + L.sh_glp, *t = sl + L.sh_t, *dz = sl + L.sh_dz;
+    float *hst = (float*)(sl + L.sh_st), *logits = (float*)ws(L.wh_logits), *rowloss = (float*)ws(L.wh_rowloss);
+    const int cap = cfg.mlm_max_rows > 0 && cfg.mlm_max_rows < T ? cfg.mlm_max_rows : T;
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_mlm_compact((const int32_t*)aux, T, cap, NP, V, rows_idx, tgt, info, q); }));
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_gather_rows(dt, xin, rows_idx, r, NP, H, T, q); }));
+    {
+      GemmArgs ga{};
+      ga.A = r; ga.lda = H; ga.B = w(L.hWt); ga.ldb = H; ga.b_kstrided = 1; ga.bias = w(L.hbt);
+      ga.C = gl; ga.C2 = glp; ga.ldc = H; ga.M = NP; ga.N = H; ga.K = H; ga.epi = EPI_BIAS | EPI_GELU;
+      TRY(gemm(KC_HEAD, ga));
+    }
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_ln_fwd(dt, gl, w(L.hG), w(L.hB), t, hst, NP, H, cfg.ln_eps, q); }));
+    {
+      GemmArgs ga{};
+      ga.A = t; ga.lda = H; ga.B = w(L.hEout); ga.ldb = H; ga.n_valid = V;
+      ga.C = logits; ga.ldc = VP; ga.M = NP; ga.N = VP; ga.K = H; ga.epi = EPI_OUT32;
+      TRY(gemm(KC_HEAD, ga));
+    }
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) {
+      return launch_mlm_ce(dt, logits, w(L.hbout), rows_idx, tgt, NP, V, VP, cfg.loss_scale, dz, rowloss, (float*)y, q);
+    }));
+  }
   return STAGE_OK;
 }
 
@@ -305,6 +370,47 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
   char *dy1 = ws(L.ws_dy1), *dctx = ws(L.ws_dctx);
   float* delta = (float*)ws(L.ws_delta);
   const char* dyin = (const char*)dy;
+  if (cfg.has_mlm_head) {
+    // backward of the head: dE_out, db_out, dt -> LN -> GELU gate -> dWt, dbt, dr, scattered back
+    // into a full [T,H] gradient of the encoder output (zero on rows that are not predicted)
+    const int NP = L.NP, VP = L.VP, V = cfg.vocab;
+    int32_t* rows_idx = (int32_t*)(sl + L.sh_rows);
+    char *r = sl + L.sh_r, *gl = sl + L.sh_gl, *glp = sl + L.sh_glp, *t = sl + L.sh_t, *dz = sl + L.sh_dz;
+    float *hst = (float*)(sl + L.sh_st), *part = (float*)ws(L.wh_part);
+    char *dtb = ws(L.wh_dt), *dgl = ws(L.wh_dgl), *dh = ws(L.wh_dh), *dr = ws(L.wh_dr), *dyfull = ws(L.wh_dyfull);
+    int nblk = 0;
+    {  // dE_out += dz^T t
+      GemmArgs ga{};
+      ga.A = dz; ga.lda = VP; ga.a_kstrided = 1; ga.B = t; ga.ldb = H; ga.b_kstrided = 1;
+      ga.C = gr(L.hEout); ga.ldc = H; ga.M = V; ga.N = H; ga.K = NP; ga.epi = EPI_ACC32;
+      TRY(gemm(KC_HEAD, ga));
+    }
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_colsum(dt, dz, NP, V, VP, part, gr(L.hbout), 1, 0, 0, q); }));
+    {  // dt = dz E_out
+      GemmArgs ga{};
+      ga.A = dz; ga.lda = VP; ga.B = w(L.hEout); ga.ldb = H; ga.b_kstrided = 1; ga.k_valid = V;
+      ga.C = dtb; ga.ldc = H; ga.M = NP; ga.N = H; ga.K = VP;
+      TRY(gemm(KC_HEAD, ga));
+    }
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dtb, gl, hst, w(L.hG), dgl, part, &nblk, NP, H, q); }));
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.hG), gr(L.hB), nullptr, q); }));
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_mul(dt, dgl, glp, dh, (long)NP * H, q); }));
+    {  // dWt += r^T dh
+      GemmArgs ga{};
+      ga.A = r; ga.lda = H; ga.a_kstrided = 1; ga.B = dh; ga.ldb = H; ga.b_kstrided = 1;
+      ga.C = gr(L.hWt); ga.ldc = H; ga.M = H; ga.N = H; ga.K = NP; ga.epi = EPI_ACC32;
+      TRY(gemm(KC_HEAD, ga));
+    }
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_colsum(dt, dh, NP, H, H, part, gr(L.hbt), 1, 0, 0, q); }));
+    {  // dr = dh Wt^T
+      GemmArgs ga{};
+      ga.A = dh; ga.lda = H; ga.B = w(L.hWt); ga.ldb = H; ga.C = dr; ga.ldc = H; ga.M = NP; ga.N = H; ga.K = H;
+      TRY(gemm(KC_HEAD, ga));
+    }
+    TRY(run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(dyfull, U, q); }));
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_scatter_rows(dt, dr, rows_idx, dyfull, NP, H, T, q); }));
+    dyin = dyfull;
+  }
   for (int l = cfg.n_layers - 1; l >= 0; --l) {
     const LayerParams& p = L.lp[l];
     const LayerStash& a = L.ls[l];
@@ -316,7 +422,7 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
     char *qkv = sl + a.qkv, *ctx = sl + a.ctx, *z1 = sl + a.z1, *y1 = sl + a.y1, *gp = sl + a.gp, *g = sl + a.g,
          *z2 = sl + a.z2;
     float *lse = (float*)(sl + a.lse), *st1 = (float*)(sl + a.st1), *st2 = (float*)(sl + a.st2);
-    char* dxout = l == 0 ? (char*)dx : ws(L.ws_dx[l & 1]);
+    char* dxout = l == 0 ? (cfg.has_embedding ? ws(L.we_dx0) : (char*)dx) : ws(L.ws_dx[l & 1]);
     const size_t pstride = (size_t)H * H + H;
     int nblk = 0;
     // this layer's workspace set was last read by the side work of layer l + 2
@@ -394,6 +500,20 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
     }
     dyin = dxout;
   }
+  if (cfg.has_embedding) {
+    // x = LN(e): de, the gradients of the embedding LayerNorm, then the two table gradients
+    char *de = ws(L.we_de), *esum = sl + L.slot_embsum;
+    float* part = (float*)ws(L.we_part);
+    int nblk = 0;
+    TRY(run(KC_EMBED, 0, [&](hipStream_t q) {
+      return launch_ln_bwd(dt, dyin, esum, (const float*)(sl + L.slot_embst), w(L.embG), de, part, &nblk, T, H, q);
+    }));
+    TRY(run(KC_EMBED, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.embG), gr(L.embB), nullptr, q); }));
+    TRY(run(KC_EMBED, 0, [&](hipStream_t q) {
+      return launch_embed_bwd(dt, (const int32_t*)(sl + L.slot_ids), de, gr(L.embEw), gr(L.embEp), cfg.micro_batch,
+                              cfg.seq, H, cfg.vocab, q);
+    }));
+  }
   // The task ends when both streams are done: whatever follows on the caller's stream (the next
   // forward reusing this slot, a gradient read-out) is ordered after the accumulator updates.
   TRY(join(0));
@@ -465,8 +585,6 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
                size_t arena_bytes, void* hip_stream) {
   if (!out || !cfg) return fail(STAGE_E_NULL, "out and cfg must not be NULL");
   TRY(check_config(*cfg));
-  if (cfg->has_embedding || cfg->has_mlm_head)
-    return fail(STAGE_E_CONFIG, "embedding block and MLM head are not available in this build");
   const bool dry = (cfg->flags & STAGE_FLAG_DRY_RUN) != 0;
   if (!dry && (!weights_dev || !arena_dev)) return fail(STAGE_E_NULL, "weights_dev and arena_dev must not be NULL");
   dapple_stage* h = new (std::nothrow) dapple_stage();
@@ -505,6 +623,8 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
       }
   }
   int rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->grads, h->L.grad_bytes, q); });
+  if (rc == STAGE_OK && cfg->has_mlm_head)
+    rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->ws(h->L.wh_info), 16, q); });
   if (rc != STAGE_OK) { delete h; return rc; }
   *out = h;
   return STAGE_OK;
@@ -666,6 +786,12 @@ int stage_sync(stage_handle h) {
   hipError_t e = hipStreamSynchronize(h->st);
   if (e == hipSuccess) e = hipStreamSynchronize(h->side);
   if (e != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed: %s", hipGetErrorString(e));
+  if (h->cfg.has_mlm_head) {
+    int32_t info[2] = {0, 0};
+    if (hipMemcpy(info, h->ws(h->L.wh_info), 8, hipMemcpyDeviceToHost) != hipSuccess)
+      return fail(STAGE_E_DEVICE, "hipMemcpy failed");
+    if (info[1]) return fail(STAGE_E_CONFIG, "a micro-batch predicted more rows than mlm_max_rows; the surplus was dropped");
+  }
   return STAGE_OK;
 }
 

@@ -17,10 +17,12 @@ def to_np(t):
 
 
 def c_config(cfg: I.StageConfig, max_slots, loss_scale=1.0):
+    import math
     return B.make_config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, max_slots,
                          B.DTYPE_BF16 if cfg.dtype == "bf16" else B.DTYPE_F32, cfg.has_embedding,
                          cfg.has_mlm_head, cfg.vocab if (cfg.has_embedding or cfg.has_mlm_head) else 0,
-                         cfg.max_pos if cfg.has_embedding else 0, 0, cfg.ln_eps, loss_scale)
+                         cfg.max_pos if cfg.has_embedding else 0, 0, cfg.ln_eps, loss_scale,
+                         math.ceil(0.15 * cfg.tokens) if cfg.has_mlm_head else 0)
 
 
 def oracle_stage(cfg, theta, loss_scale=1.0):
@@ -83,7 +85,7 @@ def compare(cfg, st, ref, got, tol, M):
 
     for m in range(M):
         if cfg.has_mlm_head:
-            upd(f"loss{m}", abs(got["ys"][m][0] - ref["ys"][m]) / abs(ref["ys"][m]))
+            upd(f"loss{m}", abs(float(got["ys"][m].reshape(-1)[0]) - ref["ys"][m]) / abs(ref["ys"][m]))
         else:
             upd(f"y{m}", rel_l2(got["ys"][m], ref["ys"][m].reshape(T, H)))
         if not cfg.has_embedding:

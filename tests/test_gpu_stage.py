@@ -17,11 +17,11 @@ TOL_F32, TOL_BF16 = 1e-4, 2e-2
 SEED = I.DEFAULT_SEED
 
 
-def check_config(cfg, M, K, tol):
+def check_config(cfg, M, K, tol, loss_scale=1.0):
     theta, mbs = make_inputs(cfg, SEED, M)
-    st, ref = run_oracle(cfg, theta, mbs, M, K)
-    eb = run_gpu(cfg, theta, mbs, M, K, B.ORDER_EARLY_BACKWARD)
-    gp = run_gpu(cfg, theta, mbs, M, K, B.ORDER_GPIPE)
+    st, ref = run_oracle(cfg, theta, mbs, M, K, loss_scale=loss_scale)
+    eb = run_gpu(cfg, theta, mbs, M, K, B.ORDER_EARLY_BACKWARD, loss_scale=loss_scale)
+    gp = run_gpu(cfg, theta, mbs, M, K, B.ORDER_GPIPE, loss_scale=loss_scale)
     worst = compare(cfg, st, ref, eb, tol, M)
     compare(cfg, st, ref, gp, tol, M)
     # the two orders run the same kernels on the same data and add the micro-batch
@@ -107,6 +107,48 @@ def test_repeat_runs_are_bit_identical_and_zero_grads_works():
         assert np.array_equal(r.grads.cpu().numpy(), a["grads"])
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_first_stage_with_embeddings_small(dtype):
+    # repeated ids inside a micro-batch (vocab smaller than b*s) exercise the ordered scatter-add
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    cfg = I.StageConfig(2, 256, 4, 512, 128, 2, 3, 2, dtype, has_embedding=True, vocab=97, max_pos=128, ln_eps=1e-5)
+    worst = check_config(cfg, 3, 2, tol)
+    print("embedding stage worst:", dtype, worst)
+    cfg = I.StageConfig(1, 64, 4, 128, 24, 3, 2, 1, dtype, has_embedding=True, vocab=1000, max_pos=32, ln_eps=1e-5)
+    check_config(cfg, 2, 1, tol)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_last_stage_with_mlm_head_small(dtype):
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    # vocab not a multiple of 4 or 64: padded columns, ragged tiles
+    cfg = I.StageConfig(2, 256, 4, 512, 128, 2, 3, 2, dtype, has_mlm_head=True, vocab=1022, ln_eps=1e-5)
+    worst = check_config(cfg, 3, 2, tol, loss_scale=1.0 / 117)
+    print("head stage worst:", dtype, worst)
+    cfg = I.StageConfig(1, 64, 4, 128, 24, 3, 2, 1, dtype, has_mlm_head=True, vocab=50, ln_eps=1e-5)
+    check_config(cfg, 2, 1, tol, loss_scale=0.5)
+
+
+def test_first_stage_full_shapes_reduced_M():
+    """Layer and vocabulary shapes of the first-stage configuration (12 layers, H 1024, seq 512,
+    micro-batch 2, vocab 30522), with M = 3, K = 2 so that the oracle stays within a minute."""
+    cfg = I.CONFIGS["first_stage"]
+    worst = check_config(cfg, 3, 2, TOL_BF16)
+    print("first_stage worst:", worst)
+
+
+def test_last_stage_full_shapes_reduced_M():
+    cfg = I.CONFIGS["last_stage"]
+    worst = check_config(cfg, 3, 2, TOL_BF16, loss_scale=1.0 / (3 * 154))
+    print("last_stage worst:", worst)
+
+
+def test_bert48_quarter_full_shapes_reduced_M():
+    cfg = I.CONFIGS["bert48_quarter"]
+    worst = check_config(cfg, 5, 4, TOL_BF16)
+    print("bert48_quarter worst:", worst)
 
 
 def test_bert_large_shaped_stage_full_size():
