@@ -26,8 +26,11 @@ namespace dapple {
 template <typename T>
 __device__ __forceinline__ void epilogue_store(const GemmArgs& g, long zc, long zbias, int row, int col, float t) {
   if (g.epi & EPI_BIAS) t += to_f32(((const T*)g.bias)[zbias + col]);
-  if (g.epi & EPI_ADD) t += to_f32(((const T*)g.aux)[zc + (long)row * g.ldaux + col]);
-  if (g.epi & EPI_MUL) t *= to_f32(((const T*)g.aux)[zc + (long)row * g.ldaux + col]);
+  if (g.epi & (EPI_ADD | EPI_MUL)) {
+    long ao = zc + (long)row * g.ldaux + col;
+    float x = (g.epi & EPI_AUX32) ? ((const float*)g.aux)[ao] : to_f32(((const T*)g.aux)[ao]);
+    t = (g.epi & EPI_ADD) ? t + x : t * x;
+  }
   long o = zc + (long)row * g.ldc + col;
   if (g.epi & EPI_GELU) {
     float a, b;
@@ -348,19 +351,24 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
             }
         }
         if (epi & (EPI_ADD | EPI_MUL)) {
-          bf16x4 xv[HB];
+          float4 xv[HB];
 #pragma unroll
           for (int u = 0; u < HB; ++u) {
             bool ok = rows[u] < g.M && cols[u] < g.N;
             long o = ok ? zc + (long)rows[u] * g.ldaux + cols[u] : zc;
-            xv[u] = *(const bf16x4*)((const bf16*)g.aux + o);
+            if (epi & EPI_AUX32) {
+              xv[u] = *(const float4*)((const float*)g.aux + o);
+            } else {
+              bf16x4 b4 = *(const bf16x4*)((const bf16*)g.aux + o);
+              xv[u] = make_float4((float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]);
+            }
           }
 #pragma unroll
           for (int u = 0; u < HB; ++u) {
             if (epi & EPI_ADD) {
-              t[u].x += (float)xv[u][0]; t[u].y += (float)xv[u][1]; t[u].z += (float)xv[u][2]; t[u].w += (float)xv[u][3];
+              t[u].x += xv[u].x; t[u].y += xv[u].y; t[u].z += xv[u].z; t[u].w += xv[u].w;
             } else {
-              t[u].x *= (float)xv[u][0]; t[u].y *= (float)xv[u][1]; t[u].z *= (float)xv[u][2]; t[u].w *= (float)xv[u][3];
+              t[u].x *= xv[u].x; t[u].y *= xv[u].y; t[u].z *= xv[u].z; t[u].w *= xv[u].w;
             }
           }
         }
@@ -476,7 +484,7 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
           !aligned_to(g.Cz[z], 16))
         return false;
   }
-  if ((g.epi & (EPI_ADD | EPI_MUL)) && (g.ldaux % 4 || !aligned_to(g.aux, 8))) return false;
+  if ((g.epi & (EPI_ADD | EPI_MUL)) && (g.ldaux % 4 || !aligned_to(g.aux, 16))) return false;
   if ((g.epi & EPI_BIAS) && !aligned_to(g.bias, 8)) return false;
   if ((g.epi & EPI_GELU) && !aligned_to(g.C2, 8)) return false;
   return true;

@@ -63,7 +63,7 @@ int dapple_layernorm_fwd(int dtype, const void* z, const void* gamma, const void
                          int rows, int H, float eps, void* stream) {
   if (!z || !gamma || !beta || !y || !stats) return STAGE_E_NULL;
   if (bad_dtype(dtype) || !ln_shape_ok(dtype, rows, H)) return STAGE_E_CONFIG;
-  return dev_rc(launch_ln_fwd(dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32, z, gamma, beta, y, stats, rows, H, eps,
+  return dev_rc(launch_ln_fwd(dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32, z, false, gamma, beta, y, nullptr, stats, rows, H, eps,
                               (hipStream_t)stream));
 }
 
@@ -72,7 +72,7 @@ int dapple_layernorm_bwd(int dtype, const void* dy, const void* z, const float* 
   if (!dy || !z || !stats || !gamma || !dz || !partial) return STAGE_E_NULL;
   if (bad_dtype(dtype) || !ln_shape_ok(dtype, rows, H)) return STAGE_E_CONFIG;
   int nblk = 0;
-  hipError_t e = launch_ln_bwd(dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32, dy, z, stats, gamma, dz, partial, &nblk,
+  hipError_t e = launch_ln_bwd(dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32, dy, z, false, stats, gamma, dz, partial, &nblk,
                                rows, H, (hipStream_t)stream);
   if (e != hipSuccess) return STAGE_E_DEVICE;
   return dev_rc(launch_partial_reduce(partial, nblk, 3, H, dgamma, dbeta, dbias, (hipStream_t)stream));

@@ -22,7 +22,8 @@ enum GemmEpi {
   EPI_MUL = 4,    // t *= aux[m,n]
   EPI_GELU = 8,   // C = gelu(t), C2 = gelu'(t)
   EPI_ACC32 = 16,  // C is fp32 and C += t (weight-gradient accumulation)
-  EPI_OUT32 = 32   // C is fp32 and C = t
+  EPI_OUT32 = 32,  // C is fp32 and C = t
+  EPI_AUX32 = 64   // aux is fp32 (residual stream of a bf16 stage)
 };
 
 struct GemmArgs {
@@ -72,13 +73,15 @@ hipError_t launch_attn_bwd(Dtype dt, const AttnArgs& a, hipStream_t st);
 bool attn_uses_mfma(Dtype dt, const AttnArgs& a);
 
 // ---------------------------------------------------------------- row kernels
-// y = LN(z) over the last dim (H), stats[2*r] = mean, stats[2*r+1] = rstd.
-hipError_t launch_ln_fwd(Dtype dt, const void* z, const void* gamma, const void* beta, void* y,
-                         float* stats, int rows, int H, float eps, hipStream_t st);
+// y = LN(z) over the last dim (H), stats[2*r] = mean, stats[2*r+1] = rstd.  z_f32: z is fp32
+// although the stage is bf16 (the residual stream is kept unrounded); y32 (may be NULL): an
+// fp32 copy of y for the next residual add.
+hipError_t launch_ln_fwd(Dtype dt, const void* z, bool z_f32, const void* gamma, const void* beta, void* y,
+                         float* y32, float* stats, int rows, int H, float eps, hipStream_t st);
 // dz = LN backward; partial[(blk*3 + {0,1,2})*H + c] = block partial sums of
 // dy*xhat (dgamma), dy (dbeta), dz (bias of the linear that produced z).
 // Returns the number of partial blocks through *nblk.
-hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, const float* stats,
+hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, bool z_f32, const float* stats,
                          const void* gamma, void* dz, float* partial, int* nblk, int rows, int H,
                          hipStream_t st);
 // o_v[c] += sum over blk (ascending) of partial[(blk*nvec + v)*H + c], v < nvec <= 3;

@@ -39,23 +39,38 @@ __device__ __forceinline__ void store_vec<bf16>(bf16* p, const float (&o)[8]) {
   *(bf16x8*)p = v;
 }
 
+// V consecutive elements of a tensor that is either of the io type T or fp32 (the pre-LayerNorm
+// sums of a bf16 stage are kept in fp32: the residual stream is never rounded to bf16)
+template <typename T, bool Z32>
+__device__ __forceinline__ void load_z(const void* base, long off, float (&o)[Vec<T>::N]) {
+  if (Z32) {
+#pragma unroll
+    for (int e = 0; e < Vec<T>::N; e += 4) {
+      float4 v = *(const float4*)((const float*)base + off + e);
+      o[e] = v.x; o[e + 1] = v.y; o[e + 2] = v.z; o[e + 3] = v.w;
+    }
+  } else {
+    load_vec<T>((const T*)base + off, o);
+  }
+}
+
 // ------------------------------------------------------------------ LayerNorm forward
 // one wave per row; NCH = ceil(H / (64 * VEC)) register chunks per lane
-template <typename T, int NCH>
-__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ z, const T* __restrict__ gamma,
+template <typename T, int NCH, bool Z32>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const void* __restrict__ z, const T* __restrict__ gamma,
                                                      const T* __restrict__ beta, T* __restrict__ y,
-                                                     float* __restrict__ stats, int rows, int H, float eps) {
+                                                     float* __restrict__ y32, float* __restrict__ stats, int rows,
+                                                     int H, float eps) {
   constexpr int V = Vec<T>::N;
   int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
-  const T* zr = z + (long)row * H;
   float x[NCH][V];
   float s = 0.f;
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     int col = (c * 64 + lane) * V;
     if (col < H) {
-      load_vec<T>(zr + col, x[c]);
+      load_z<T, Z32>(z, (long)row * H + col, x[c]);
 #pragma unroll
       for (int e = 0; e < V; ++e) s += x[c][e];
     }
@@ -88,6 +103,11 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ z, co
 #pragma unroll
       for (int e = 0; e < V; ++e) o[e] = (x[c][e] - mean) * rstd * g[e] + b[e];
       store_vec<T>(y + (long)row * H + col, o);
+      if (y32) {  // unrounded copy for the residual branch
+#pragma unroll
+        for (int e = 0; e < V; e += 4)
+          *(float4*)(y32 + (long)row * H + col + e) = make_float4(o[e], o[e + 1], o[e + 2], o[e + 3]);
+      }
     }
   }
 }
@@ -98,8 +118,8 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ z, co
 // waves in LDS in wave order and writes partial[(blk*3 + v)*H + col].
 constexpr int LNB_ROWS = 8;
 
-template <typename T, int NCH>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ z,
+template <typename T, int NCH, bool Z32>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const void* __restrict__ z,
                                                      const float* __restrict__ stats, const T* __restrict__ gamma,
                                                      T* __restrict__ dz, float* __restrict__ partial, int rows, int H) {
   constexpr int V = Vec<T>::N;
@@ -128,7 +148,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
       int col = (c * 64 + lane) * V;
       if (live[q] && col < H) {
         load_vec<T>(dy + (long)row * H + col, d[q][c]);
-        load_vec<T>(z + (long)row * H + col, zz[q][c]);
+        load_z<T, Z32>(z, (long)row * H + col, zz[q][c]);
       } else {
 #pragma unroll
         for (int e = 0; e < V; ++e) d[q][c][e] = zz[q][c][e] = 0.f;
@@ -294,14 +314,14 @@ static int nch_for(int H) {
   return (H + per - 1) / per;
 }
 
-template <typename T>
-static hipError_t ln_fwd_t(const void* z, const void* g, const void* b, void* y, float* stats, int rows, int H,
-                           float eps, hipStream_t st) {
+template <typename T, bool Z32>
+static hipError_t ln_fwd_t(const void* z, const void* g, const void* b, void* y, float* y32, float* stats, int rows,
+                           int H, float eps, hipStream_t st) {
   dim3 grid((rows + 3) / 4), blk(256);
   int n = nch_for<T>(H);
-#define LNF(N)                                                                                              \
-  hipLaunchKernelGGL((ln_fwd_kernel<T, N>), grid, blk, 0, st, (const T*)z, (const T*)g, (const T*)b, (T*)y, \
-                     stats, rows, H, eps)
+#define LNF(N)                                                                                                \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, N, Z32>), grid, blk, 0, st, z, (const T*)g, (const T*)b, (T*)y, y32, stats, \
+                     rows, H, eps)
   if (n <= 1) LNF(1);
   else if (n <= 2) LNF(2);
   else if (n <= 4) LNF(4);
@@ -311,44 +331,46 @@ static hipError_t ln_fwd_t(const void* z, const void* g, const void* b, void* y,
   return hipGetLastError();
 }
 
-hipError_t launch_ln_fwd(Dtype dt, const void* z, const void* gamma, const void* beta, void* y, float* stats,
-                         int rows, int H, float eps, hipStream_t st) {
-  return dt == DT_BF16 ? ln_fwd_t<bf16>(z, gamma, beta, y, stats, rows, H, eps, st)
-                       : ln_fwd_t<float>(z, gamma, beta, y, stats, rows, H, eps, st);
+hipError_t launch_ln_fwd(Dtype dt, const void* z, bool z_f32, const void* gamma, const void* beta, void* y,
+                         float* y32, float* stats, int rows, int H, float eps, hipStream_t st) {
+  if (dt != DT_BF16) return ln_fwd_t<float, false>(z, gamma, beta, y, y32, stats, rows, H, eps, st);
+  return z_f32 ? ln_fwd_t<bf16, true>(z, gamma, beta, y, y32, stats, rows, H, eps, st)
+               : ln_fwd_t<bf16, false>(z, gamma, beta, y, y32, stats, rows, H, eps, st);
 }
 
-template <typename T, int N>
+template <typename T, int N, bool Z32>
 static hipError_t ln_bwd_launch(const void* dy, const void* z, const float* stats, const void* g, void* dz,
                                 float* partial, int nb, int rows, int H, hipStream_t st) {
   static bool attr = false;
   if (!attr) {  // up to 96 KiB of LDS for the widest rows
-    hipError_t e = hipFuncSetAttribute((const void*)ln_bwd_kernel<T, N>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       12 * 64 * Vec<T>::N * N * 4);
+    hipError_t e = hipFuncSetAttribute((const void*)ln_bwd_kernel<T, N, Z32>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 12 * 64 * Vec<T>::N * N * 4);
     if (e != hipSuccess) return e;
     attr = true;
   }
   size_t sh = (size_t)12 * H * sizeof(float);
-  hipLaunchKernelGGL((ln_bwd_kernel<T, N>), dim3(nb), dim3(256), sh, st, (const T*)dy, (const T*)z, stats,
-                     (const T*)g, (T*)dz, partial, rows, H);
+  hipLaunchKernelGGL((ln_bwd_kernel<T, N, Z32>), dim3(nb), dim3(256), sh, st, (const T*)dy, z, stats, (const T*)g,
+                     (T*)dz, partial, rows, H);
   return hipGetLastError();
 }
 
-template <typename T>
+template <typename T, bool Z32>
 static hipError_t ln_bwd_t(const void* dy, const void* z, const float* stats, const void* g, void* dz,
                            float* partial, int nb, int rows, int H, hipStream_t st) {
   int n = nch_for<T>(H);
-  if (n <= 1) return ln_bwd_launch<T, 1>(dy, z, stats, g, dz, partial, nb, rows, H, st);
-  if (n <= 2) return ln_bwd_launch<T, 2>(dy, z, stats, g, dz, partial, nb, rows, H, st);
-  if (n <= 4) return ln_bwd_launch<T, 4>(dy, z, stats, g, dz, partial, nb, rows, H, st);
+  if (n <= 1) return ln_bwd_launch<T, 1, Z32>(dy, z, stats, g, dz, partial, nb, rows, H, st);
+  if (n <= 2) return ln_bwd_launch<T, 2, Z32>(dy, z, stats, g, dz, partial, nb, rows, H, st);
+  if (n <= 4) return ln_bwd_launch<T, 4, Z32>(dy, z, stats, g, dz, partial, nb, rows, H, st);
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, const float* stats, const void* gamma, void* dz,
-                         float* partial, int* nblk, int rows, int H, hipStream_t st) {
+hipError_t launch_ln_bwd(Dtype dt, const void* dy, const void* z, bool z_f32, const float* stats, const void* gamma,
+                         void* dz, float* partial, int* nblk, int rows, int H, hipStream_t st) {
   int nb = (rows + LNB_ROWS - 1) / LNB_ROWS;
   *nblk = nb;
-  return dt == DT_BF16 ? ln_bwd_t<bf16>(dy, z, stats, gamma, dz, partial, nb, rows, H, st)
-                       : ln_bwd_t<float>(dy, z, stats, gamma, dz, partial, nb, rows, H, st);
+  if (dt != DT_BF16) return ln_bwd_t<float, false>(dy, z, stats, gamma, dz, partial, nb, rows, H, st);
+  return z_f32 ? ln_bwd_t<bf16, true>(dy, z, stats, gamma, dz, partial, nb, rows, H, st)
+               : ln_bwd_t<bf16, false>(dy, z, stats, gamma, dz, partial, nb, rows, H, st);
 }
 
 hipError_t launch_partial_reduce(const float* partial, int nblk, int nvec, int H, float* o0, float* o1, float* o2,

@@ -66,6 +66,7 @@ struct Layout {
   size_t wh_logits = 0, wh_rowloss = 0, wh_dt = 0, wh_dgl = 0, wh_dh = 0, wh_dr = 0, wh_dyfull = 0, wh_part = 0,
          wh_info = 0;
   size_t we_dx0 = 0, we_de = 0, we_part = 0;
+  size_t ws_y1f = 0, ws_yf[2] = {0, 0};  // fp32 copies of LayerNorm outputs for the residual adds (bf16 stages)
   size_t slot_bytes = 0;
   // workspace (bytes)
   // buffers the side stream reads exist twice (layers alternate between the sets)
@@ -93,6 +94,8 @@ int check_config(const stage_config& c) {
   if (c.has_embedding || c.has_mlm_head) {
     if (c.vocab < 1) return fail(STAGE_E_CONFIG, "vocab must be positive");
     if (c.has_embedding && c.max_pos < c.seq) return fail(STAGE_E_CONFIG, "max_pos (%d) smaller than seq (%d)", c.max_pos, c.seq);
+    if (((long)c.micro_batch * c.seq) % 4) return fail(STAGE_E_CONFIG, "micro_batch * seq must be a multiple of 4 for this stage kind");
+    if (c.mlm_max_rows < 0) return fail(STAGE_E_CONFIG, "mlm_max_rows must not be negative");
   }
   if ((long)c.micro_batch * c.seq > (1 << 24)) return fail(STAGE_E_CONFIG, "micro_batch * seq too large");
   return STAGE_OK;
@@ -130,8 +133,9 @@ void build_layout(const stage_config& c, Layout& L) {
     auto& s = L.ls[l];
     s.qkv = stake(3 * U);   // q, k, v contiguous (3U is a multiple of 256 whenever U is)
     s.lse = stake((size_t)c.micro_batch * c.n_heads * c.seq * 4);
-    s.ctx = stake(U); s.z1 = stake(U); s.st1 = stake(2 * T * 4); s.y1 = stake(U);
-    s.gp = stake(T * F * E); s.g = stake(T * F * E); s.z2 = stake(U); s.st2 = stake(2 * T * 4);
+    // z1, z2 (the pre-LayerNorm sums = the residual stream) are fp32 whatever the stage dtype
+    s.ctx = stake(U); s.z1 = stake(T * H * 4); s.st1 = stake(2 * T * 4); s.y1 = stake(U);
+    s.gp = stake(T * F * E); s.g = stake(T * F * E); s.z2 = stake(T * H * 4); s.st2 = stake(2 * T * 4);
     bool keep_y = l + 1 < c.n_layers || c.has_mlm_head;
     s.y = keep_y ? stake(U) : 0;
   }
@@ -149,6 +153,9 @@ void build_layout(const stage_config& c, Layout& L) {
   auto wtake = [&](size_t bytes) { size_t o = wo; wo += align_up(bytes); return o; };
   L.ws_dx[0] = wtake(U); L.ws_dx[1] = wtake(U); L.ws_dy1 = wtake(U); L.ws_dctx = wtake(U);
   L.ws_delta = wtake((size_t)c.micro_batch * c.n_heads * c.seq * 4);
+  if (c.dtype == STAGE_DTYPE_BF16) {
+    L.ws_y1f = wtake(T * H * 4); L.ws_yf[0] = wtake(T * H * 4); L.ws_yf[1] = wtake(T * H * 4);
+  }
   const size_t ln_part = ((T + 7) / 8) * 3 * H * 4, cs_rows = (T + 63) / 64;
   for (int p = 0; p < 2; ++p) {
     L.ws_dz2[p] = wtake(U); L.ws_du[p] = wtake(T * F * E); L.ws_dz1[p] = wtake(U); L.ws_dqkv[p] = wtake(3 * U);
@@ -270,7 +277,14 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
   char* sl = slot(s);
   (void)aux;
   const char* xin = sl + L.slot_x0;
+  // bf16 stages keep the residual stream unrounded: the pre-LayerNorm sums z1, z2 and the copy
+  // of each LayerNorm output that feeds the next residual add are fp32; only GEMM operands are bf16
+  const bool mixed = dt == DT_BF16;
+  const void* resid = xin;            // residual input of the next attention block
+  bool resid_f32 = false;
   if (cfg.has_embedding) {
+    resid = mixed ? (const void*)ws(L.ws_yf[1]) : (const void*)xin;
+    resid_f32 = mixed;
     // x = LN(E_w[id] + E_p[pos]); the ids and the pre-LN sum are kept for the backward
     int32_t* ids = (int32_t*)(sl + L.slot_ids);
     char* esum = sl + L.slot_embsum;
@@ -279,7 +293,8 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
       return launch_embed_gather(dt, ids, w(L.embEw), w(L.embEp), esum, T, cfg.seq, H, cfg.vocab, q);
     }));
     TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) {
-      return launch_ln_fwd(dt, esum, w(L.embG), w(L.embB), sl + L.slot_x0, (float*)(sl + L.slot_embst), T, H, cfg.ln_eps, q);
+      return launch_ln_fwd(dt, esum, false, w(L.embG), w(L.embB), sl + L.slot_x0, mixed ? (float*)ws(L.ws_yf[1]) : nullptr,
+                           (float*)(sl + L.slot_embst), T, H, cfg.ln_eps, q);
     }));
   } else {
     TRY(run(KC_COPY, 0, [&](hipStream_t q) { return launch_copy(sl + L.slot_x0, x, U, q); }));
@@ -308,10 +323,14 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
     {  // z1 = x + ctx Wo + bo
       GemmArgs ga{};
       ga.A = ctx; ga.lda = H; ga.B = w(p.Wo); ga.ldb = H; ga.b_kstrided = 1; ga.bias = w(p.bo);
-      ga.aux = xin; ga.ldaux = H; ga.C = z1; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H; ga.epi = EPI_BIAS | EPI_ADD;
+      ga.aux = resid; ga.ldaux = H; ga.C = z1; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H;
+      ga.epi = EPI_BIAS | EPI_ADD | (mixed ? EPI_OUT32 : 0) | (resid_f32 ? EPI_AUX32 : 0);
       TRY(gemm(KC_GEMM_FWD, ga));
     }
-    TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) { return launch_ln_fwd(dt, z1, w(p.ln1g), w(p.ln1b), y1, st1, T, H, cfg.ln_eps, q); }));
+    float* y1f = mixed ? (float*)ws(L.ws_y1f) : nullptr;
+    TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) {
+      return launch_ln_fwd(dt, z1, mixed, w(p.ln1g), w(p.ln1b), y1, y1f, st1, T, H, cfg.ln_eps, q);
+    }));
     {  // g = GELU(y1 W1 + b1), gp = GELU'(y1 W1 + b1)
       GemmArgs ga{};
       ga.A = y1; ga.lda = H; ga.B = w(p.W1); ga.ldb = F; ga.b_kstrided = 1; ga.bias = w(p.b1);
@@ -321,11 +340,17 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
     {  // z2 = y1 + g W2 + b2
       GemmArgs ga{};
       ga.A = g; ga.lda = F; ga.B = w(p.W2); ga.ldb = H; ga.b_kstrided = 1; ga.bias = w(p.b2);
-      ga.aux = y1; ga.ldaux = H; ga.C = z2; ga.ldc = H; ga.M = T; ga.N = H; ga.K = F; ga.epi = EPI_BIAS | EPI_ADD;
+      ga.aux = mixed ? (const void*)y1f : (const void*)y1; ga.ldaux = H; ga.C = z2; ga.ldc = H; ga.M = T; ga.N = H;
+      ga.K = F; ga.epi = EPI_BIAS | EPI_ADD | (mixed ? EPI_OUT32 | EPI_AUX32 : 0);
       TRY(gemm(KC_GEMM_FWD, ga));
     }
-    TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) { return launch_ln_fwd(dt, z2, w(p.ln2g), w(p.ln2b), yout, st2, T, H, cfg.ln_eps, q); }));
+    float* yf = (mixed && l + 1 < cfg.n_layers) ? (float*)ws(L.ws_yf[l & 1]) : nullptr;
+    TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) {
+      return launch_ln_fwd(dt, z2, mixed, w(p.ln2g), w(p.ln2b), yout, yf, st2, T, H, cfg.ln_eps, q);
+    }));
     xin = yout;
+    resid = yf ? (const void*)yf : (const void*)yout;
+    resid_f32 = yf != nullptr;
   }
   if (cfg.has_mlm_head) {
     // gather the predicted rows, t = LN(GELU(r Wt + bt)), z = t E_out^T (+ b_out inside the
@@ -343,7 +368,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
       ga.C = gl; ga.C2 = glp; ga.ldc = H; ga.M = NP; ga.N = H; ga.K = H; ga.epi = EPI_BIAS | EPI_GELU;
       TRY(gemm(KC_HEAD, ga));
     }
-    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_ln_fwd(dt, gl, w(L.hG), w(L.hB), t, hst, NP, H, cfg.ln_eps, q); }));
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_ln_fwd(dt, gl, false, w(L.hG), w(L.hB), t, nullptr, hst, NP, H, cfg.ln_eps, q); }));
     {
       GemmArgs ga{};
       ga.A = t; ga.lda = H; ga.B = w(L.hEout); ga.ldb = H; ga.n_valid = V;
@@ -392,7 +417,7 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
       ga.C = dtb; ga.ldc = H; ga.M = NP; ga.N = H; ga.K = VP;
       TRY(gemm(KC_HEAD, ga));
     }
-    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dtb, gl, hst, w(L.hG), dgl, part, &nblk, NP, H, q); }));
+    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dtb, gl, false, hst, w(L.hG), dgl, part, &nblk, NP, H, q); }));
     TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.hG), gr(L.hB), nullptr, q); }));
     TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_mul(dt, dgl, glp, dh, (long)NP * H, q); }));
     {  // dWt += r^T dh
@@ -429,7 +454,7 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
     if (l + 2 < cfg.n_layers) TRY(join(l + 2));
 
     // y = LN(z2): dz2, and block partial sums for the gradients of ln2 gain/shift and of b2
-    TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dyin, z2, st2, w(p.ln2g), dz2, part_ln2, &nblk, T, H, q); }));
+    TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dyin, z2, dt == DT_BF16, st2, w(p.ln2g), dz2, part_ln2, &nblk, T, H, q); }));
     TRY(fork(l, 0));
     TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln2, nblk, 3, H, gr(p.ln2g), gr(p.ln2b), gr(p.b2), q); }));
     {  // dW2 += g^T dz2
@@ -458,7 +483,7 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
       ga.C = dy1; ga.ldc = H; ga.M = T; ga.N = H; ga.K = F; ga.epi = EPI_ADD;
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
-    TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dy1, z1, st1, w(p.ln1g), dz1, part_ln1, &nblk, T, H, q); }));
+    TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dy1, z1, dt == DT_BF16, st1, w(p.ln1g), dz1, part_ln1, &nblk, T, H, q); }));
     TRY(fork(l, 2));
     TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln1, nblk, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), q); }));
     {  // dctx = dz1 Wo^T
@@ -506,7 +531,7 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
     float* part = (float*)ws(L.we_part);
     int nblk = 0;
     TRY(run(KC_EMBED, 0, [&](hipStream_t q) {
-      return launch_ln_bwd(dt, dyin, esum, (const float*)(sl + L.slot_embst), w(L.embG), de, part, &nblk, T, H, q);
+      return launch_ln_bwd(dt, dyin, esum, false, (const float*)(sl + L.slot_embst), w(L.embG), de, part, &nblk, T, H, q);
     }));
     TRY(run(KC_EMBED, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.embG), gr(L.embB), nullptr, q); }));
     TRY(run(KC_EMBED, 0, [&](hipStream_t q) {
