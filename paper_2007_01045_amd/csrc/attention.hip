@@ -54,6 +54,7 @@ __global__ void attn_fwd_plain(AttnArgs a, float scale2) {
     o = fmaf(p, to_f32(vb[(long)j * a.H + dd]), o);
   }
   ((T*)a.ctx)[((long)bi * a.s + qi) * a.H + hh * a.d + dd] = from_f32<T>(o / l);
+  if (a.ctx32) a.ctx32[((long)bi * a.s + qi) * a.H + hh * a.d + dd] = o / l;
   if (dd == 0) a.lse[((long)bi * a.A + hh) * a.s + qi] = m + log2f(l);
 }
 
@@ -67,7 +68,12 @@ __global__ void attn_delta_kernel(AttnArgs a) {
   const T* o = (const T*)a.ctx + row * a.H + hh * a.d;
   const T* g = (const T*)a.dctx + row * a.H + hh * a.d;
   float t = 0.f;
-  for (int e = 0; e < a.d; ++e) t = fmaf(to_f32(o[e]), to_f32(g[e]), t);
+  if (a.ctx32) {
+    const float* o32 = a.ctx32 + row * a.H + hh * a.d;
+    for (int e = 0; e < a.d; ++e) t = fmaf(o32[e], to_f32(g[e]), t);
+  } else {
+    for (int e = 0; e < a.d; ++e) t = fmaf(to_f32(o[e]), to_f32(g[e]), t);
+  }
   int bi = row / a.s, qi = row % a.s;
   a.delta[((long)bi * a.A + hh) * a.s + qi] = t;
 }
@@ -263,6 +269,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnArgs a, float scale2) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) ov[e] = (bf16)(o[db][4 * blk + e] * inv);
         *(bf16x4*)(C + db * 32 + 8 * blk + 4 * h) = ov;
+        if (a.ctx32)
+          *(float4*)(a.ctx32 + hb + (long)qrow * a.H + db * 32 + 8 * blk + 4 * h) =
+              make_float4(o[db][4 * blk] * inv, o[db][4 * blk + 1] * inv, o[db][4 * blk + 2] * inv, o[db][4 * blk + 3] * inv);
       }
     if (h == 0) a.lse[((long)bi * a.A + hh) * a.s + qrow] = m + log2f(l);
   }
@@ -382,9 +391,19 @@ __global__ __launch_bounds__(256) void attn_dq_mfma(AttnArgs a, float scale2, fl
   for (int kk = 0; kk < 4; ++kk) {
     qf[kk] = frag_global(Q, qrow, qok, a.H, kk, lane);
     gf[kk] = frag_global(G, qrow, qok, a.H, kk, lane);
-    bf16x8 of = frag_global(O, qrow, qok, a.H, kk, lane);
+    if (a.ctx32) {
+      if (qok) {
+        const float* o32 = a.ctx32 + hb + (long)qrow * a.H + kk * 16 + 8 * h;
+        float4 lo = *(const float4*)o32, hi = *(const float4*)(o32 + 4);
+        float ov[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
-    for (int e = 0; e < 8; ++e) Dq = fmaf((float)gf[kk][e], (float)of[e], Dq);
+        for (int e = 0; e < 8; ++e) Dq = fmaf((float)gf[kk][e], ov[e], Dq);
+      }
+    } else {
+      bf16x8 of = frag_global(O, qrow, qok, a.H, kk, lane);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) Dq = fmaf((float)gf[kk][e], (float)of[e], Dq);
+    }
   }
   Dq += __shfl_xor(Dq, 32, 64);
   if (qok && h == 0) a.delta[((long)bi * a.A + hh) * a.s + qrow] = Dq;

@@ -59,9 +59,13 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g);
 // q,k,v,ctx,dq,dk,dv,dctx: [b*s, H] row-major, head h in columns [h*d, (h+1)*d).
 // lse: [b, A, s] fp32, log2-domain logsumexp of the scaled logits.
 // delta: [b, A, s] fp32 scratch, rowsum(dctx * ctx) per head.
+// ctx32 (may be NULL): unrounded fp32 copy of ctx, written by the forward and used by the
+// backward for delta -- an error in delta shifts a whole row of dS coherently, so a bf16 ctx
+// there costs percents of accuracy in dq and dk although ctx itself is accurate to 2^-9.
 struct AttnArgs {
   const void *q, *k, *v;
   void* ctx;
+  float* ctx32;
   float* lse;
   const void* dctx;
   void *dq, *dk, *dv;

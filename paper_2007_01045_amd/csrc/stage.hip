@@ -48,7 +48,7 @@ struct LayerParams {
 };
 // byte offsets of one layer's stash inside an activation slot
 struct LayerStash {
-  size_t qkv, lse, ctx, z1, st1, y1, gp, g, z2, st2, y;
+  size_t qkv, lse, ctx, ctx32, z1, st1, y1, gp, g, z2, st2, y;
 };
 
 struct Layout {
@@ -134,7 +134,7 @@ void build_layout(const stage_config& c, Layout& L) {
     s.qkv = stake(3 * U);   // q, k, v contiguous (3U is a multiple of 256 whenever U is)
     s.lse = stake((size_t)c.micro_batch * c.n_heads * c.seq * 4);
     // z1, z2 (the pre-LayerNorm sums = the residual stream) are fp32 whatever the stage dtype
-    s.ctx = stake(U); s.z1 = stake(T * H * 4); s.st1 = stake(2 * T * 4); s.y1 = stake(U);
+    s.ctx = stake(U); s.ctx32 = c.dtype == STAGE_DTYPE_BF16 ? stake(T * H * 4) : 0; s.z1 = stake(T * H * 4); s.st1 = stake(2 * T * 4); s.y1 = stake(U);
     s.gp = stake(T * F * E); s.g = stake(T * F * E); s.z2 = stake(T * H * 4); s.st2 = stake(2 * T * 4);
     bool keep_y = l + 1 < c.n_layers || c.has_mlm_head;
     s.y = keep_y ? stake(U) : 0;
@@ -316,6 +316,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
     {
       AttnArgs aa{};
       aa.q = qkv; aa.k = qkv + U; aa.v = qkv + 2 * U; aa.ctx = ctx; aa.lse = lse;
+      aa.ctx32 = dt == DT_BF16 ? (float*)(sl + a.ctx32) : nullptr;
       aa.b = cfg.micro_batch; aa.s = cfg.seq; aa.A = cfg.n_heads; aa.d = H / cfg.n_heads; aa.H = H;
       double fl = 4.0 * T * (double)cfg.seq * H;
       TRY(run(KC_ATTN_FWD, fl, [&](hipStream_t q) { return launch_attn_fwd(dt, aa, q); }));
@@ -494,6 +495,7 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
     {
       AttnArgs aa{};
       aa.q = qkv; aa.k = qkv + U; aa.v = qkv + 2 * U; aa.ctx = ctx; aa.lse = lse; aa.dctx = dctx;
+      aa.ctx32 = dt == DT_BF16 ? (float*)(sl + a.ctx32) : nullptr;
       aa.dq = dqkv; aa.dk = dqkv + U; aa.dv = dqkv + 2 * U; aa.delta = delta;
       aa.b = cfg.micro_batch; aa.s = cfg.seq; aa.A = cfg.n_heads; aa.d = H / cfg.n_heads; aa.H = H;
       double fl = 8.0 * T * (double)cfg.seq * H;
