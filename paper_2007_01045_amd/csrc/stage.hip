@@ -195,6 +195,10 @@ struct dapple_stage {
   float* grads;
   hipStream_t st;         // the caller's stream: the critical path (forward; backward data gradients)
   hipStream_t side = nullptr;  // library-owned: weight / bias / LayerNorm gradient work of a backward task
+  hipStream_t fwd = nullptr;   // library-owned: forward tasks inside stage_run_schedule
+  hipStream_t cur = nullptr;   // where the task being enqueued puts its main-line kernels (st or fwd)
+  std::vector<hipEvent_t> ev_f, ev_b;  // per slot: forward done (fwd lane), backward done (caller's stream)
+  hipEvent_t ev_start = nullptr;
   std::vector<hipEvent_t> ev;  // per layer: 4 "inputs ready" events (main -> side) + 1 "layer done" (side -> main)
   std::vector<int> slot_of_mb;   // slot -> micro-batch id, -1 = free
   int live = 0, peak_live = 0;
@@ -211,7 +215,7 @@ struct dapple_stage {
 
   // run one launcher; with profiling on, bracket it with two events
   template <typename Fn>
-  int run(int cls, double flops, Fn&& fn) { return run_on(st, cls, flops, fn); }
+  int run(int cls, double flops, Fn&& fn) { return run_on(cur, cls, flops, fn); }
 
   // main -> side: the side stream may start once the main stream has passed this point
   int fork(int layer, int which) {
@@ -262,7 +266,7 @@ struct dapple_stage {
     if (g.n_valid == 0) g.n_valid = g.N;
     if (g.batch == 0) g.batch = 1;
     double flops = 2.0 * g.M * g.N * (double)g.K * g.batch;
-    return run_on(on_side ? side : st, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); });
+    return run_on(on_side ? side : cur, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); });
   }
 
   int forward(int s, const void* x, void* y, const void* aux);
@@ -642,13 +646,25 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
       delete h;
       return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
     }
+    if (hipStreamCreateWithFlags(&h->fwd, hipStreamNonBlocking) != hipSuccess) {
+      delete h;
+      return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
+    }
     h->ev.resize((size_t)cfg->n_layers * 5);
-    for (auto& e : h->ev)
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+    h->ev_f.resize(cfg->max_slots);
+    h->ev_b.resize(cfg->max_slots);
+    std::vector<hipEvent_t*> all;
+    for (auto& e : h->ev) all.push_back(&e);
+    for (auto& e : h->ev_f) all.push_back(&e);
+    for (auto& e : h->ev_b) all.push_back(&e);
+    all.push_back(&h->ev_start);
+    for (hipEvent_t* e : all)
+      if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) {
         delete h;
         return fail(STAGE_E_DEVICE, "hipEventCreate failed");
       }
   }
+  h->cur = h->st;
   int rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->grads, h->L.grad_bytes, q); });
   if (rc == STAGE_OK && cfg->has_mlm_head)
     rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->ws(h->L.wh_info), 16, q); });
@@ -662,10 +678,15 @@ int stage_destroy(stage_handle h) {
   if (!h->dry) {
     (void)hipStreamSynchronize(h->st);
     if (h->side) (void)hipStreamSynchronize(h->side);
+    if (h->fwd) (void)hipStreamSynchronize(h->fwd);
   }
   for (auto& e : h->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
   for (auto& e : h->ev) (void)hipEventDestroy(e);
+  for (auto& e : h->ev_f) (void)hipEventDestroy(e);
+  for (auto& e : h->ev_b) (void)hipEventDestroy(e);
+  if (h->ev_start) (void)hipEventDestroy(h->ev_start);
   if (h->side) (void)hipStreamDestroy(h->side);
+  if (h->fwd) (void)hipStreamDestroy(h->fwd);
   delete h;
   return STAGE_OK;
 }
@@ -741,12 +762,58 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
       if (!xs[m] || !ys[m] || (need_dy && !dys[m]) || (need_dx && !dxs[m]) || (need_aux && !auxs[m]))
         return fail(STAGE_E_NULL, "a device pointer of micro-batch %d is NULL", m);
   }
+  // Two lanes: forward tasks go to the library's forward stream, backward tasks stay on the
+  // caller's stream, so that F_{j+K} runs beside B_{j+1} instead of between B_j and B_{j+1}.
+  // Dependences kept: F_m -> B_m; B_m -> the forward that reuses its slot; forwards among
+  // themselves and backwards among themselves in list order (which fixes the order of every
+  // gradient accumulation).  The early-backward order needs no more than that; the other orders
+  // are run strictly as listed (a backward waits for every forward listed before it).
+  const bool lanes = !h->dry && !h->profiling;
+  const bool strict = order != STAGE_ORDER_EARLY_BACKWARD;
+  std::vector<char> b_pending(h->cfg.max_slots, 0);
+  int last_f_slot = -1;
+  auto hip_ok = [](hipError_t e) { return e == hipSuccess ? STAGE_OK : fail(STAGE_E_DEVICE, "%s", hipGetErrorString(e)); };
+  if (lanes) {
+    TRY(hip_ok(hipEventRecord(h->ev_start, h->st)));
+    TRY(hip_ok(hipStreamWaitEvent(h->fwd, h->ev_start, 0)));
+  }
+  int rc = STAGE_OK;
   for (int32_t op : ops) {
     int m = (op > 0 ? op : -op) - 1;
-    if (op > 0) TRY(stage_fwd(h, m, xs ? xs[m] : nullptr, ys ? ys[m] : nullptr, auxs ? auxs[m] : nullptr));
-    else TRY(stage_bwd(h, m, dys ? dys[m] : nullptr, dxs ? dxs[m] : nullptr));
+    if (op > 0) {
+      if (lanes) {
+        int s = find_slot(h, -1);  // the slot stage_fwd is about to take
+        if (s >= 0 && b_pending[s]) {
+          if ((rc = hip_ok(hipStreamWaitEvent(h->fwd, h->ev_b[s], 0))) != STAGE_OK) break;
+          b_pending[s] = 0;
+        }
+        h->cur = h->fwd;
+        rc = stage_fwd(h, m, xs[m], ys[m], auxs ? auxs[m] : nullptr);
+        h->cur = h->st;
+        if (rc != STAGE_OK) break;
+        if ((rc = hip_ok(hipEventRecord(h->ev_f[s], h->fwd))) != STAGE_OK) break;
+        last_f_slot = s;
+      } else if ((rc = stage_fwd(h, m, xs ? xs[m] : nullptr, ys ? ys[m] : nullptr, auxs ? auxs[m] : nullptr)) != STAGE_OK) break;
+    } else {
+      int s = -1;
+      if (lanes) {
+        s = find_slot(h, m);
+        int w = strict ? last_f_slot : s;
+        if (w >= 0 && (rc = hip_ok(hipStreamWaitEvent(h->st, h->ev_f[w], 0))) != STAGE_OK) break;
+      }
+      if ((rc = stage_bwd(h, m, dys ? dys[m] : nullptr, dxs ? dxs[m] : nullptr)) != STAGE_OK) break;
+      if (lanes) {
+        if ((rc = hip_ok(hipEventRecord(h->ev_b[s], h->st))) != STAGE_OK) break;
+        b_pending[s] = 1;
+      }
+    }
   }
-  return STAGE_OK;
+  // the caller's stream ends behind everything the forward lane was given, also on an error
+  if (lanes && last_f_slot >= 0) {
+    int rc2 = hip_ok(hipStreamWaitEvent(h->st, h->ev_f[last_f_slot], 0));
+    if (rc == STAGE_OK) rc = rc2;
+  }
+  return rc;
 }
 
 int stage_grads(stage_handle h, void** grads_dev, uint64_t* n) {
