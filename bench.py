@@ -23,6 +23,12 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 
+# HBM-side bytes per gemm_mfma_kernel launch (average over the 528 launches of a step), from the
+# rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in profiles/gemm_mfma_bert_large_pmc_traffic.md,
+# each counter scaled by what it reads for the library's copy kernel of known size (1.990 / 1.000).
+# Counters cannot be read from inside this process, so the figure is carried here per workload.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"bert_large": 65505188}
+
 
 def stage_flops(cfg, M):
     """Algorithmic flops of one iteration: per layer and micro-batch the forward is
@@ -159,7 +165,8 @@ def main():
                                   "ratio": peak_bytes["early_backward"] / peak_bytes["gpipe"]},
         "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel (all linear-layer products: fwd, dgrad, wgrad)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
                      "launches_per_step": g_n / prof_steps, "avg_launch_us": g_ms * 1e3 / max(g_n, 1)},
         "kernel_classes": classes,
     }
