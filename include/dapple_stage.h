@@ -30,9 +30,10 @@
  *     max_slots activation slots, workspace).
  *   - all device work is ordered in the HIP stream given to stage_init; no call
  *     synchronises the stream except stage_sync.  (A backward task also uses a second,
- *     library-owned stream for the gradient-accumulator kernels; it is forked from and
- *     joined back into the caller's stream inside the task, so the caller's stream order
- *     still covers everything.)  Buffers passed to a call must stay valid until the
+ *     library-owned stream for the gradient-accumulator kernels, and stage_run_schedule
+ *     a third one for its forward tasks; both are forked from and joined back into the
+ *     caller's stream inside the call, so the caller's stream order still covers
+ *     everything.)  Buffers passed to a call must stay valid until the
  *     stream has passed that call.
  *   - every call returns 0 on success or a negative STAGE_E_* code; nothing throws
  *     or aborts.  stage_last_error() gives a message for the last failure of the
@@ -135,7 +136,12 @@ int stage_schedule_ops(int M, int K, int order, int32_t* ops_out, int capacity);
  * auxs: host arrays of M device pointers (arrays that do not apply may be NULL).
  * order EXPLICIT takes explicit_ops/n_ops in the encoding above; the list is
  * validated (each F before its B, every micro-batch once, at most K resident)
- * before anything is enqueued. */
+ * before anything is enqueued.
+ * The early-backward order is executed as the dependence graph that defines it
+ * (the control edges B_m -> F_{m+K} of section V-C plus F_m -> B_m, forwards in
+ * list order, backwards in list order): forward tasks go to the library's forward
+ * stream and overlap the backward tasks on the caller's stream.  The other two
+ * orders are executed strictly as listed.  Results do not depend on the overlap. */
 int stage_run_schedule(stage_handle h, int M, int K, int order,
                        const void* const* xs, const void* const* dys,
                        void* const* ys, void* const* dxs, const void* const* auxs,
