@@ -51,6 +51,9 @@ typedef struct {
   int64_t sA, sB, sC, sBias;
   int32_t k_valid;
   int32_t epi;
+  int32_t tile;   /* 0 = automatic; 1..7 = a specific tile shape and LDS ring depth of the MFMA kernel
+                   * (1: 256x256/2, 2: 256x128/3, 3: 128x128/2, 4: 128x128/4, 5: 128x64/2, 6: 128x64/3,
+                   * 7: 128x64/4), for tests and tuning */
 } dapple_gemm_desc;
 
 /* Returns 1 if the bf16 MFMA kernel takes this problem, 0 if the plain kernel does. */

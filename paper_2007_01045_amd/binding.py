@@ -49,7 +49,7 @@ class dapple_gemm_desc(C.Structure):
                 ("a_kstrided", C.c_int32), ("b_kstrided", C.c_int32), ("kseg_len", C.c_int32),
                 ("segA", C.c_int64), ("segB", C.c_int64), ("batch", C.c_int32),
                 ("sA", C.c_int64), ("sB", C.c_int64), ("sC", C.c_int64), ("sBias", C.c_int64),
-                ("k_valid", C.c_int32), ("epi", C.c_int32)]
+                ("k_valid", C.c_int32), ("epi", C.c_int32), ("tile", C.c_int32)]
 
 
 # every symbol the two headers declare: name -> (restype, argtypes)

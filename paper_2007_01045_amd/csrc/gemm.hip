@@ -16,6 +16,7 @@
 //    kernel does not take.
 #include <cstdlib>
 #include <type_traits>
+#include <utility>
 
 #include "device_common.h"
 #include "kernels.h"
@@ -92,11 +93,29 @@ typedef __attribute__((__vector_size__(4 * sizeof(int)))) int int4v;
 // per wave instruction against 8 and 8 unswizzled); they are applied on the global
 // side (which chunk a lane fetches), since the LDS side of a direct load is fixed
 // to lane order.
+//
+// A wave issues one instruction every few clocks, and a k-step of a 64x64 wave tile is
+// only 16 MFMAs: the loop is bound by instruction issue unless everything around the
+// MFMAs is a handful of instructions.  So every per-lane address is computed once,
+// before the loop (global side: voff; LDS side: FragAddr), the ring slot enters as an
+// instruction immediate (the k-loop is unrolled over the ring), and the global cursor
+// is a buffer resource in scalar registers that advances by two scalar adds per k-step.
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
 template <int R, bool KS, int NW>
 struct OperandTile {
   static constexpr int NI = R * 8 / (64 * NW);  // load instructions per wave per k-step
   static constexpr int LDS_ELEMS = R * BK;
-    static_assert(R * 8 % (64 * NW) == 0, "tile rows must split evenly over the waves");
+  static constexpr int LDS_BYTES = LDS_ELEMS * 2;
+  static_assert(R * 8 % (64 * NW) == 0, "tile rows must split evenly over the waves");
   int voff[NI];  // per-lane byte offset of each load inside the k-step's slab
 
   // chunk swizzle of k row k of a k-strided tile: rows of 256 B or more rotate by 64 B per
@@ -116,42 +135,68 @@ struct OperandTile {
       }
     }
   }
-  // base: first element of this k-step's slab (k-contiguous: operand + k0; k-strided:
-  // operand + k0*ld); avail: bytes from base to the end of the valid operand region
-  __device__ __forceinline__ void load(const bf16* base, long avail, bf16* S, int wave) const {
-    unsigned rec = avail <= 0 ? 0u : (avail > 0x7fffffffL ? 0x7fffffffu : (unsigned)avail);
-    // buffer resource: base address, stride 0, num_records (bytes), raw 32-bit format
-    uint64_t b = (uint64_t)base;
-    int4v rs;
-    rs[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
-    rs[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(b >> 32) & 0xffffu));
-    rs[2] = __builtin_amdgcn_readfirstlane((int)rec);
+  // Request one k-step's slab.  rs: buffer resource whose base is the slab's first element
+  // and whose num_records is the number of valid bytes from there (0 = nothing to read);
+  // LDS_OFF: byte offset of the tile in LDS (ring slot and operand; a constant);
+  // wave_off = wave * 1024.  Issued from inline assembly on purpose: through the compiler
+  // builtin every LDS read that follows waits for ALL outstanding loads (the compiler cannot
+  // tell the ring slots apart), which would undo the multi-stage pipeline.  The kernel keeps
+  // its own count instead (s_waitcnt vmcnt(n) before the workgroup barrier).
+  template <int LDS_OFF>
+  __device__ __forceinline__ void load(int4v rs, int wave_off) const {
+    // uniform already; this only tells the compiler so (no instruction when it is in SGPRs)
+    rs[0] = __builtin_amdgcn_readfirstlane(rs[0]);
+    rs[1] = __builtin_amdgcn_readfirstlane(rs[1]);
+    rs[2] = __builtin_amdgcn_readfirstlane(rs[2]);
     rs[3] = (int)BUF_RSRC_FLAGS;
-    // The loads are issued from inline assembly on purpose: through the compiler builtin
-    // every LDS read that follows waits for ALL outstanding loads (the compiler cannot tell
-    // the ring slots apart), which would undo the multi-stage pipeline.  The kernel keeps
-    // its own count instead (s_waitcnt vmcnt(n) before the workgroup barrier).
+    wave_off = __builtin_amdgcn_readfirstlane(wave_off);
+    // Two hazards the hardware does not interlock and the compiler cannot see inside an asm
+    // block (CDNA3 ISA guide, manually inserted wait states): a scalar write of the resource
+    // registers needs 5 wait states before a vector-memory instruction reads them (the compiler
+    // assembles the 4-register tuple right before the first block: s_nop 4), and a scalar write
+    // of M0 needs 1 before the LDS-direct load that uses it (s_nop 0).
+    asm volatile("s_nop 4\n\ts_add_u32 m0, %0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds"
+                 :
+                 : "s"(wave_off), "i"(LDS_OFF), "v"(voff[0]), "s"(rs)
+                 : "memory", "m0", "scc");
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      unsigned dst = (unsigned)(uintptr_t)(S + (j * NW + wave) * 512);
-      asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+    for (int j = 1; j < NI; ++j)
+      asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds"
                    :
-                   : "s"(__builtin_amdgcn_readfirstlane((int)dst)), "v"(voff[j]), "s"(rs)
-                   : "memory", "m0");
-    }
+                   : "s"(wave_off), "i"(LDS_OFF + j * NW * 1024), "v"(voff[j]), "s"(rs)
+                   : "memory", "m0", "scc");
   }
-  // MFMA fragment for rows r0..r0+31 (lane & 31), k = kk*16 + 8*(lane>>5) + 0..7
-  static __device__ __forceinline__ bf16x8 frag(const bf16* S, int r0, int kk, int lane) {
+};
+
+// LDS byte addresses of a lane's MFMA fragments, relative to the operand's tile:
+// rows w0 + 32*blk + (lane & 31), k = kk*16 + 8*(lane>>5) + 0..7.  Everything that depends
+// on blk, kk or the ring slot beyond these few registers is an instruction immediate.
+template <int R, bool KS, int NB>
+struct FragAddr {
+  unsigned a[KS ? NB : 4];
+  __device__ __forceinline__ void init(int w0, int lane) {
     if (!KS) {
-      int row = r0 + (lane & 31);
-      int kc = kk * 2 + (lane >> 5);
-      return *(const bf16x8*)(S + row * BK + ((kc ^ ((row >> 1) & 7)) << 3));
+      int r = lane & 31, sw = (r >> 1) & 7;  // w0 is a multiple of 32: the swizzle sees lane bits only
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) a[kk] = (unsigned)((w0 + r) * (BK * 2) + (((kk * 2 + (lane >> 5)) ^ sw) << 4));
     } else {
       int i16 = lane & 15, g16 = (lane >> 4) & 1, h = lane >> 5;
-      int krow = kk * 16 + 8 * h + (i16 >> 2);
-      int col = r0 + 16 * g16 + 4 * (i16 & 3);
-      int sw = kswz(i16 >> 2);  // depends on krow & 3 only: the same for krow + 4
-      const bf16* p = S + krow * R + (((col >> 3) ^ sw) << 3) + (col & 7);
+      int krow = 8 * h + (i16 >> 2);
+      int sw = OperandTile<R, KS, 4>::kswz(i16 >> 2);  // depends on krow & 3 only
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        int col = w0 + 32 * b + 16 * g16 + 4 * (i16 & 3);
+        a[b] = (unsigned)((krow * R + (((col >> 3) ^ sw) << 3) + (col & 7)) * 2);
+      }
+    }
+  }
+  // OFF: byte offset of the operand's tile in LDS (a constant)
+  template <int OFF, int BLK, int KK>
+  __device__ __forceinline__ bf16x8 get(const unsigned char* smem) const {
+    if (!KS) {
+      return *(const bf16x8*)(smem + a[KK] + (OFF + BLK * 32 * BK * 2));
+    } else {
+      const bf16* p = (const bf16*)(smem + a[BLK] + (OFF + KK * 16 * R * 2));
       return join8(lds_read_tr16(p), lds_read_tr16(p + 4 * R));
     }
   }
@@ -178,7 +223,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   typedef typename CFG::TB TB;
   constexpr int MI = CFG::MI, NI = CFG::NI;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  bf16* lds = (bf16*)smem;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -230,19 +274,54 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   TB tb;
   ta.init(g.lda, m0, wave, lane);
   tb.init(g.ldb, n0, wave, lane);
+  FragAddr<BM, AKS, MI> fa;
+  FragAddr<BN, BKS, NI> fb;
+  fa.init(wm0, lane);
+  fb.init(wn0, lane);
+  const int wave_off = wave * 1024;
 
-  // request k-tile kt into ring slot kt % NS; a tile past the end requests nothing (zero
-  // records: every lane is out of range), which keeps the number of outstanding requests
-  // per tile constant so that one s_waitcnt count fits every iteration
-  auto issue_loads = [&](int kt) {
-    int seg = kt / tiles_per_seg;
-    int k0 = (kt - seg * tiles_per_seg) * BK;
-    long aoff = AKS ? (long)k0 * g.lda : (long)k0;
-    long boff = BKS ? (long)k0 * g.ldb : (long)k0;
-    bf16* S = lds + (kt % NS) * CFG::STAGE_ELEMS;
-    bool live = kt < nk;
-    ta.load(Ab + (live ? seg * g.segA + aoff : 0), live ? a_ext - aoff * 2 : 0, S, wave);
-    tb.load(Bb + (live ? seg * g.segB + boff : 0), live ? b_ext - boff * 2 : 0, S + TA::LDS_ELEMS, wave);
+  // Global cursors, all in scalar registers: one buffer resource per operand whose base is
+  // the first element of the next k-step's slab and whose num_records is what may still be
+  // read from there.  A k-step forward is base += step, records -= step; at the end of a
+  // K segment the base jumps to the next segment and the records start over.
+  const int a_step = AKS ? BK * g.lda * 2 : BK * 2, b_step = BKS ? BK * g.ldb * 2 : BK * 2;
+  const long a_jump = g.segA * 2 - (long)(tiles_per_seg - 1) * a_step;
+  const long b_jump = g.segB * 2 - (long)(tiles_per_seg - 1) * b_step;
+  int4v ars, brs;
+  auto set_base = [](int4v& rs, uint64_t p) {
+    rs[0] = (int)(uint32_t)p;
+    rs[1] = (int)(uint32_t)(p >> 32);  // a device address has no bits above 47: stride and swizzle fields stay 0
+  };
+  auto get_base = [](const int4v& rs) { return ((uint64_t)(uint32_t)rs[1] << 32) | (uint32_t)rs[0]; };
+  set_base(ars, (uint64_t)Ab);
+  set_base(brs, (uint64_t)Bb);
+  ars[0] = __builtin_amdgcn_readfirstlane(ars[0]);
+  ars[1] = __builtin_amdgcn_readfirstlane(ars[1]);
+  brs[0] = __builtin_amdgcn_readfirstlane(brs[0]);
+  brs[1] = __builtin_amdgcn_readfirstlane(brs[1]);
+  ars[2] = __builtin_amdgcn_readfirstlane((int)a_ext);
+  brs[2] = __builtin_amdgcn_readfirstlane((int)b_ext);
+  ars[3] = brs[3] = (int)BUF_RSRC_FLAGS;
+  // Branch-free on purpose: with control flow inside the k-loop the accumulators get
+  // copied between register files at every merge point.
+  int seg_left = tiles_per_seg, tiles_left = nk;
+  auto advance = [&]() {
+    --seg_left;
+    --tiles_left;
+    const bool cross = seg_left == 0, more = tiles_left > 0;
+    set_base(ars, get_base(ars) + (uint64_t)(cross ? a_jump : (long)a_step));
+    set_base(brs, get_base(brs) + (uint64_t)(cross ? b_jump : (long)b_step));
+    // past the last k-tile the cursor reads nothing: such a request fills its slot with zeros
+    ars[2] = more ? (cross ? (int)a_ext : max(ars[2] - a_step, 0)) : 0;
+    brs[2] = more ? (cross ? (int)b_ext : max(brs[2] - b_step, 0)) : 0;
+    seg_left = cross ? tiles_per_seg : seg_left;
+  };
+  // request the next k-tile into ring slot S
+  auto issue_loads = [&](auto S) {
+    constexpr int off = decltype(S)::value * CFG::STAGE_ELEMS * 2;
+    ta.template load<off>(ars, wave_off);
+    tb.template load<off + TA::LDS_BYTES>(brs, wave_off);
+    advance();
   };
 
   f32x16 acc[MI][NI];
@@ -253,20 +332,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // Software pipeline.  Global->LDS: tile kt+2 is requested as soon as every wave has
-  // left tile kt's buffer, so a request has a whole tile of MFMA time to land.
-  // LDS->registers: the fragments of k-step kk+1 are requested before the MFMAs of
-  // k-step kk are issued (two fragment sets), so the matrix cores never wait for an
-  // LDS round trip except once per tile.
+  // Software pipeline.  Global->LDS: a k-tile is requested NS-1 iterations before it is
+  // used, as soon as every wave has left the ring slot it goes to.  LDS->registers: the
+  // fragments of k-step kk+1 are requested before the MFMAs of k-step kk are issued (two
+  // fragment sets), so the matrix cores wait for an LDS round trip only once per tile.
   struct Frags {
     bf16x8 a[MI], b[NI];
   };
-  auto load_frags = [&](Frags& f, const bf16* As, int kk) {
-    const bf16* Bs = As + TA::LDS_ELEMS;
-#pragma unroll
-    for (int i = 0; i < MI; ++i) f.a[i] = TA::frag(As, wm0 + i * 32, kk, lane);
-#pragma unroll
-    for (int j = 0; j < NI; ++j) f.b[j] = TB::frag(Bs, wn0 + j * 32, kk, lane);
+  auto load_frags = [&](Frags& f, auto S, auto KK) {
+    constexpr int off = decltype(S)::value * CFG::STAGE_ELEMS * 2, kk = decltype(KK)::value;
+    static_for<MI>([&](auto I) { f.a[decltype(I)::value] = fa.template get<off, decltype(I)::value, kk>(smem); });
+    static_for<NI>([&](auto J) { f.b[decltype(J)::value] = fb.template get<off + TA::LDS_BYTES, decltype(J)::value, kk>(smem); });
   };
   auto mfma_step = [&](const Frags& f) {
 #pragma unroll
@@ -275,34 +351,49 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
       for (int j = 0; j < NI; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
   };
+  auto compute = [&](auto S) {
+    Frags f0, f1;
+    load_frags(f0, S, std::integral_constant<int, 0>{});
+    load_frags(f1, S, std::integral_constant<int, 1>{});
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(f0, S, std::integral_constant<int, 2>{});
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(f1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(f1, S, std::integral_constant<int, 3>{});
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(f1);
+  };
+  static_assert(BK == 64, "compute() spells out the four k-steps of a tile");
 
-#pragma unroll
-  for (int t = 0; t < NS - 1; ++t) issue_loads(t);
-
-  // vmcnt(N): at most N of this wave's requests still in flight; requests complete in
-  // order, so N = (NS - 2) * LOADS_PER_TILE means "tile kt has landed"
+  // The loop runs whole turns of the ring: K is padded to a multiple of NS k-tiles with
+  // tiles that read nothing (zeros in LDS add nothing), and every iteration requests a tile,
+  // so the count of requests in flight is the same in every iteration.
+  // vmcnt(N): at most N of this wave's requests still in flight; requests complete in order,
+  // so N = (NS - 2) * LOADS_PER_TILE means "tile kt has landed"
   constexpr int INFLIGHT = (NS - 2) * CFG::LOADS_PER_TILE;
   static_assert(INFLIGHT < 64, "vmcnt is a 6-bit counter");
-  constexpr int WAIT_TILE = (INFLIGHT & 15) | ((INFLIGHT >> 4) << 14) | 0x0F70;  // expcnt, lgkmcnt: no wait
-
-  Frags cur, nxt;
-  for (int kt = 0; kt < nk; ++kt) {
-    const bf16* As = lds + (kt % NS) * CFG::STAGE_ELEMS;
-    __builtin_amdgcn_s_waitcnt(WAIT_TILE);
-    __builtin_amdgcn_s_barrier();  // every wave's part of tile kt is in LDS; tile kt-1's slot is free
-    issue_loads(kt + NS - 1);
-    load_frags(cur, As, 0);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) load_frags(nxt, As, kk + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_step(cur);
-      __builtin_amdgcn_sched_barrier(0);
-      cur = nxt;
-    }
+  // ... and lgkmcnt(0): this wave's LDS reads of the previous tile must have EXECUTED, not just
+  // been issued, before the barrier lets other waves refill that slot (a request that reads
+  // nothing delivers its zeros within a few clocks)
+  constexpr int WAIT_TILE = (INFLIGHT & 15) | ((INFLIGHT >> 4) << 14) | 0x0070;  // expcnt: no wait
+  static_for<NS - 1>([&](auto T) { issue_loads(T); });
+  const int turns = (nk + NS - 1) / NS;
+  for (int t = 0; t < turns; ++t) {
+    static_for<NS>([&](auto S) {
+      __builtin_amdgcn_sched_barrier(0);  // no LDS read of the previous tile may sink below the barrier
+      __builtin_amdgcn_s_waitcnt(WAIT_TILE);
+      __builtin_amdgcn_s_barrier();  // every wave's part of this tile is in LDS; the previous tile's slot is free
+      issue_loads(std::integral_constant<int, (decltype(S)::value + NS - 1) % NS>{});
+      compute(S);
+    });
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) tail requests before LDS is reused
-  __syncthreads();
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // the tail requests (they read nothing) must be done before LDS is reused
+  __syncthreads();  // every wave has read its last fragments: LDS can be reused
 
   // epilogue: per wave, 32 output rows at a time through an fp32 LDS staging tile that
   // turns "a lane owns 4 columns of one row" into row-contiguous stores.
@@ -437,8 +528,9 @@ DAPPLE_GEMM_INST(256, 256, 2, 2, 2)
 DAPPLE_GEMM_INST(256, 128, 2, 2, 3)
 DAPPLE_GEMM_INST(128, 128, 2, 2, 2)
 DAPPLE_GEMM_INST(128, 128, 2, 2, 4)
+DAPPLE_GEMM_INST(128, 64, 2, 2, 2)
 DAPPLE_GEMM_INST(128, 64, 2, 2, 3)
-DAPPLE_GEMM_INST(128, 64, 2, 2, 6)
+DAPPLE_GEMM_INST(128, 64, 2, 2, 4)
 #undef DAPPLE_GEMM_INST
 
 // ------------------------------------------------------------------ host side
@@ -484,6 +576,13 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
           !aligned_to(g.Cz[z], 16))
         return false;
   }
+  {  // the kernel counts the readable bytes of an operand segment in a 32-bit buffer field
+    const int kv = g.k_valid > 0 ? g.k_valid : g.K, mv = g.m_valid > 0 ? g.m_valid : g.M, nv = g.n_valid > 0 ? g.n_valid : g.N;
+    const long a_ext = g.a_kstrided ? ((long)(kv - 1) * g.lda + mv) * 2 : ((long)(mv - 1) * g.lda + g.kseg_len) * 2;
+    const long b_ext = g.b_kstrided ? ((long)(kv - 1) * g.ldb + nv) * 2 : ((long)(nv - 1) * g.ldb + g.kseg_len) * 2;
+    if (a_ext > 0x7fffffffL || b_ext > 0x7fffffffL) return false;
+    if ((long)BK * g.lda * 2 > 0x7fffffffL || (long)BK * g.ldb * 2 > 0x7fffffffL) return false;
+  }
   if ((g.epi & (EPI_ADD | EPI_MUL)) && (g.ldaux % 4 || !aligned_to(g.aux, 16))) return false;
   if ((g.epi & EPI_BIAS) && !aligned_to(g.bias, 8)) return false;
   if ((g.epi & EPI_GELU) && !aligned_to(g.C2, 8)) return false;
@@ -493,20 +592,31 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
 hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;
   if (gemm_uses_mfma(dt, g)) {
-    // tuning override: DAPPLE_GEMM_TILE = 0 (256x256, 4 waves), 1 (256x128), 2 (128x128), 3 (128x64)
-    static const int force = [] { const char* e = getenv("DAPPLE_GEMM_TILE"); return e ? atoi(e) : -1; }();
-    if (force == 0) return launch_mfma_layout<256, 256, 2, 2, 2>(g, st);
-    if (force == 1) return launch_mfma_layout<256, 128, 2, 2, 3>(g, st);
-    if (force == 2) return launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
-    if (force == 3) return launch_mfma_layout<128, 64, 2, 2, 3>(g, st);
-    if (force == 4) return launch_mfma_layout<128, 128, 2, 2, 4>(g, st);
-    if (force == 5) return launch_mfma_layout<128, 64, 2, 2, 6>(g, st);
-    // tile choice (measured on the BERT-Large-shaped stage): 128x128 tiles (two LDS stages,
-    // two workgroups per CU) when there are at least 192 of them, else 128x64 tiles with a
-    // three-stage ring to keep all CUs busy
+    // a specific configuration: GemmArgs::tile, else the environment variable DAPPLE_GEMM_TILE
+    // (same numbering), for tests and tuning
+    static const int env_tile = [] { const char* e = getenv("DAPPLE_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    switch (g.tile ? g.tile : env_tile) {
+      case 1: return launch_mfma_layout<256, 256, 2, 2, 2>(g, st);
+      case 2: return launch_mfma_layout<256, 128, 2, 2, 3>(g, st);
+      case 3: return launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
+      case 4: return launch_mfma_layout<128, 128, 2, 2, 4>(g, st);
+      case 5: return launch_mfma_layout<128, 64, 2, 2, 2>(g, st);
+      case 6: return launch_mfma_layout<128, 64, 2, 2, 3>(g, st);
+      case 7: return launch_mfma_layout<128, 64, 2, 2, 4>(g, st);
+      default: break;
+    }
+    // tile choice (measured on the BERT-Large-shaped stage with its three streams running):
+    // 128x128 tiles with two LDS stages when there are at least 192 of them, else 128x64 tiles
+    // with a three-stage ring to keep all CUs busy.  Deeper rings are faster for a product that
+    // runs alone but cost more in co-residency with the other streams' kernels than they gain.
+    // DAPPLE_GEMM_NS_SMALL (2, 3, 4) and DAPPLE_GEMM_NS_MID (2, 4) override the ring depths.
     long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
-    if (t128 >= 192) return launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
-    return launch_mfma_layout<128, 64, 2, 2, 3>(g, st);
+    static const int ns_small = [] { const char* e = getenv("DAPPLE_GEMM_NS_SMALL"); return e ? atoi(e) : 3; }();
+    static const int ns_mid = [] { const char* e = getenv("DAPPLE_GEMM_NS_MID"); return e ? atoi(e) : 2; }();
+    if (t128 > 256) return launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
+    if (t128 >= 192) return ns_mid == 4 ? launch_mfma_layout<128, 128, 2, 2, 4>(g, st) : launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
+    if (ns_small == 2) return launch_mfma_layout<128, 64, 2, 2, 2>(g, st);
+    return ns_small == 4 ? launch_mfma_layout<128, 64, 2, 2, 4>(g, st) : launch_mfma_layout<128, 64, 2, 2, 3>(g, st);
   }
   dim3 blk(32, 8);
   dim3 grid((g.N + 31) / 32, (g.M + 7) / 8, g.batch);

@@ -25,7 +25,7 @@ int dapple_gemm(int dtype, const dapple_gemm_desc* d, void* stream) {
   g.a_kstrided = d->a_kstrided; g.b_kstrided = d->b_kstrided;
   g.kseg_len = d->kseg_len ? d->kseg_len : d->K; g.segA = d->segA; g.segB = d->segB;
   g.batch = d->batch ? d->batch : 1; g.sA = d->sA; g.sB = d->sB; g.sC = d->sC; g.sBias = d->sBias;
-  g.k_valid = d->k_valid ? d->k_valid : d->K; g.epi = d->epi;
+  g.k_valid = d->k_valid ? d->k_valid : d->K; g.epi = d->epi; g.tile = d->tile;
   g.m_valid = d->M; g.n_valid = d->N;
   if (g.K % g.kseg_len) return STAGE_E_CONFIG;
   Dtype dt = dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32;

@@ -199,6 +199,7 @@ struct dapple_stage {
   hipStream_t cur = nullptr;   // where the task being enqueued puts its main-line kernels (st or fwd)
   std::vector<hipEvent_t> ev_f, ev_b;  // per slot: forward done (fwd lane), backward done (caller's stream)
   hipEvent_t ev_start = nullptr;
+  bool serial = false, no_side = false;
   std::vector<hipEvent_t> ev;  // per layer: 4 "inputs ready" events (main -> side) + 1 "layer done" (side -> main)
   std::vector<int> slot_of_mb;   // slot -> micro-batch id, -1 = free
   int live = 0, peak_live = 0;
@@ -642,7 +643,16 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
   h->slot_of_mb.assign(cfg->max_slots, -1);
   if (!dry) {
     // default priority on purpose; the side stream never outlives the handle
-    if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) {
+    // DAPPLE_SERIAL=1 (a debugging switch) puts every kernel on the caller's stream
+    {
+      const char* e = getenv("DAPPLE_SERIAL");   // 1: no side lane and no forward lane; 2: no forward lane; 3: no side lane
+      int v = e ? atoi(e) : 0;
+      h->serial = v == 1 || v == 2;
+      h->no_side = v == 1 || v == 3;
+    }
+    if (h->no_side) {
+      h->side = h->st;
+    } else if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) {
       delete h;
       return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
     }
@@ -685,7 +695,7 @@ int stage_destroy(stage_handle h) {
   for (auto& e : h->ev_f) (void)hipEventDestroy(e);
   for (auto& e : h->ev_b) (void)hipEventDestroy(e);
   if (h->ev_start) (void)hipEventDestroy(h->ev_start);
-  if (h->side) (void)hipStreamDestroy(h->side);
+  if (h->side && h->side != h->st) (void)hipStreamDestroy(h->side);
   if (h->fwd) (void)hipStreamDestroy(h->fwd);
   delete h;
   return STAGE_OK;
@@ -768,7 +778,7 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
   // themselves and backwards among themselves in list order (which fixes the order of every
   // gradient accumulation).  The early-backward order needs no more than that; the other orders
   // are run strictly as listed (a backward waits for every forward listed before it).
-  const bool lanes = !h->dry && !h->profiling;
+  const bool lanes = !h->dry && !h->profiling && !h->serial;
   const bool strict = order != STAGE_ORDER_EARLY_BACKWARD;
   std::vector<char> b_pending(h->cfg.max_slots, 0);
   int last_f_slot = -1;

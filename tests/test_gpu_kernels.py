@@ -27,7 +27,7 @@ TOL = {B.DTYPE_BF16: 6e-3, B.DTYPE_F32: 2e-5}
 TD = {B.DTYPE_BF16: torch.bfloat16, B.DTYPE_F32: torch.float32}
 
 
-def gemm_case(dtype, M, N, K, akS, bkS, epi, batch=1, nseg=1, expect_mfma=None):
+def gemm_case(dtype, M, N, K, akS, bkS, epi, batch=1, nseg=1, expect_mfma=None, tile=0):
     bf = dtype == B.DTYPE_BF16
     td = TD[dtype]
     ks = K // nseg
@@ -58,6 +58,7 @@ def gemm_case(dtype, M, N, K, akS, bkS, epi, batch=1, nseg=1, expect_mfma=None):
     d.kseg_len, d.segA, d.segB = ks, M * ks, N * ks
     d.batch, d.sA, d.sB, d.sC, d.sBias = batch, nseg * M * ks, nseg * N * ks, M * N, N
     d.epi = epi
+    d.tile = tile
     if epi & B.EPI_ACC32:
         dC = dev(C0, torch.float32)
         want = [C0 + t]
@@ -78,6 +79,18 @@ def gemm_case(dtype, M, N, K, akS, bkS, epi, batch=1, nseg=1, expect_mfma=None):
         assert rel_l2(g, w) < TOL[dtype], (M, N, K, akS, bkS, epi, rel_l2(g, w))
         # element-wise: no element may be off by more than a few roundings of the largest value
         assert np.abs(g - w).max() < (3e-2 if bf else 1e-4) * max(np.abs(w).max(), 1.0)
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7])
+def test_gemm_mfma_every_tile_shape_and_ring_depth(tile):
+    # K = 64 * (1, 2, 3, 5, 7, 8): shorter than the ring, a multiple of no ring depth, and longer;
+    # ragged M and N; both operand layouts; a segmented K
+    for K in (64, 128, 192, 320, 448, 512):
+        gemm_case(B.DTYPE_BF16, 328, 200, K, False, True, B.EPI_BIAS, expect_mfma=True, tile=tile)
+    gemm_case(B.DTYPE_BF16, 264, 136, 320, True, True, B.EPI_ACC32, expect_mfma=True, tile=tile)
+    gemm_case(B.DTYPE_BF16, 264, 136, 448, False, False, B.EPI_ADD, expect_mfma=True, tile=tile)
+    gemm_case(B.DTYPE_BF16, 200, 264, 3 * 192, False, False, B.EPI_ADD, nseg=3, expect_mfma=True, tile=tile)
+    gemm_case(B.DTYPE_BF16, 136, 264, 320, True, False, 0, batch=3, expect_mfma=True, tile=tile)
 
 
 @pytest.mark.parametrize("akS", [False, True])
