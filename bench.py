@@ -95,8 +95,12 @@ def main():
     results = {}
     peak_bytes = {}
     runner = None
-    for order_name, order, slots in (("gpipe", B.ORDER_GPIPE, M), ("early_backward", B.ORDER_EARLY_BACKWARD, K)):
-        r = B.StageRunner(c_config(cfg, slots), theta)
+    # GPipe order with M slots; early-backward order with K slots; and the latter with re-computation
+    # (a resident micro-batch keeps its input only and the backward task re-runs the forward)
+    for order_name, order, slots, flags in (("gpipe", B.ORDER_GPIPE, M, 0),
+                                            ("early_backward_recompute", B.ORDER_EARLY_BACKWARD, K, B.FLAG_RECOMPUTE),
+                                            ("early_backward", B.ORDER_EARLY_BACKWARD, K, 0)):
+        r = B.StageRunner(c_config(cfg, slots, flags=flags), theta)
         xs = [r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
         dys = [r.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
         ys = [r.empty_act() for _ in range(M)]
@@ -168,6 +172,12 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
                      "launches_per_step": g_n / prof_steps, "avg_launch_us": g_ms * 1e3 / max(g_n, 1)},
+        "recompute": {"samples_per_s": M * cfg.micro_batch / results["early_backward_recompute"],
+                      "ms_per_step": results["early_backward_recompute"] * 1e3,
+                      "peak_activation_bytes": peak_bytes["early_backward_recompute"],
+                      "throughput_vs_stored": sec / results["early_backward_recompute"],
+                      "memory_vs_stored": peak_bytes["early_backward_recompute"] / peak_bytes["early_backward"],
+                      "memory_vs_gpipe_order": peak_bytes["early_backward_recompute"] / peak_bytes["gpipe"]},
         "kernel_classes": classes,
     }
     if not args.no_cpu_baseline:

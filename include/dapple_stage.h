@@ -71,8 +71,17 @@ enum {
 
 enum { STAGE_ORDER_GPIPE = 0, STAGE_ORDER_EARLY_BACKWARD = 1, STAGE_ORDER_EXPLICIT = 2 };
 enum { STAGE_DTYPE_F32 = 0, STAGE_DTYPE_BF16 = 1 };
-enum { STAGE_FLAG_DRY_RUN = 1 }; /* host bookkeeping only: no kernel is launched and
-                                    device pointers may be NULL (for CPU-side tests) */
+enum {
+  STAGE_FLAG_DRY_RUN = 1,   /* host bookkeeping only: no kernel is launched and device pointers may
+                               be NULL (for CPU-side tests) */
+  STAGE_FLAG_RECOMPUTE = 2  /* re-computation (section VI-E, Table VI's "+ RC" rows): a resident
+                               micro-batch keeps only the stage's input (token ids on a first stage)
+                               and its targets; stage_bwd re-runs the forward from them before it goes
+                               backward.  slot_bytes shrinks to that; two activation buffers of the
+                               full size (one for the forward tasks, one for the backward tasks) are
+                               part of workspace_bytes.  Gradients and outputs are bit-identical to
+                               the stage without the flag. */
+};
 
 typedef struct {
   int32_t n_layers, hidden, n_heads, ffn, seq, micro_batch; /* L, H, A, F, s, b */
@@ -100,7 +109,8 @@ typedef struct {
 
 typedef struct {
   uint64_t slot_bytes;
-  uint64_t peak_activation_bytes; /* peak_live_slots * slot_bytes */
+  uint64_t peak_activation_bytes; /* peak_live_slots * slot_bytes (+ the two activation buffers
+                                     under STAGE_FLAG_RECOMPUTE) */
   int32_t live_slots, peak_live_slots;
   uint64_t fwd_tasks, bwd_tasks, kernel_launches;
 } stage_stats_t;

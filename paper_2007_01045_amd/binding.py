@@ -20,6 +20,7 @@ STAGE_E_NOT_RESIDENT, STAGE_E_DUP_MB, STAGE_E_BAD_ORDER, STAGE_E_DEVICE = -5, -6
 ORDER_GPIPE, ORDER_EARLY_BACKWARD, ORDER_EXPLICIT = 0, 1, 2
 DTYPE_F32, DTYPE_BF16 = 0, 1
 FLAG_DRY_RUN = 1
+FLAG_RECOMPUTE = 2
 EPI_BIAS, EPI_ADD, EPI_MUL, EPI_GELU, EPI_ACC32 = 1, 2, 4, 8, 16
 
 

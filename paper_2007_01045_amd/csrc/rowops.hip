@@ -272,14 +272,21 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, in
 #pragma unroll
   for (int e = 0; e < V; ++e) acc[e] = 0.f;
   if (col < cols) {
-    int r0 = blockIdx.y * CS_ROWS;
-    for (int rr = wave; rr < CS_ROWS; rr += 4) {
-      int row = r0 + rr;
-      if (row >= rows) break;
-      float x[V];
-      load_vec<T>(X + (long)row * ld + col, x);
+    // all of the wave's loads are issued before the first add (rows past the end re-read the
+    // last row and are masked), so the kernel is bound by bandwidth instead of by 16 round trips
+    const int r0 = blockIdx.y * CS_ROWS;
+    constexpr int RPW = CS_ROWS / 4;
+    float x[RPW][V];
 #pragma unroll
-      for (int e = 0; e < V; ++e) acc[e] += x[e];
+    for (int q = 0; q < RPW; ++q) {
+      int row = r0 + wave + 4 * q;
+      load_vec<T>(X + (long)(row < rows ? row : rows - 1) * ld + col, x[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < RPW; ++q) {
+      const float m = (r0 + wave + 4 * q) < rows ? 1.f : 0.f;
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] += m * x[q][e];
     }
   }
 #pragma unroll

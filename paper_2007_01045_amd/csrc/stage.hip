@@ -65,9 +65,16 @@ struct Layout {
   size_t sh_rows = 0, sh_tgt = 0, sh_r = 0, sh_gl = 0, sh_glp = 0, sh_st = 0, sh_t = 0, sh_dz = 0;
   size_t wh_logits = 0, wh_rowloss = 0, wh_dt = 0, wh_dgl = 0, wh_dh = 0, wh_dr = 0, wh_dyfull = 0, wh_part = 0,
          wh_info = 0;
+  size_t wh_logits2 = 0, wh_rowloss2 = 0, wh_info2 = 0;  // second set: the forward re-run inside a backward task
   size_t we_dx0 = 0, we_de = 0, we_part = 0;
-  size_t ws_y1f = 0, ws_yf[2] = {0, 0};  // fp32 copies of LayerNorm outputs for the residual adds (bf16 stages)
+  // fp32 copies of LayerNorm outputs for the residual adds (bf16 stages); set 1: the forward re-run
+  // inside a backward task (re-computation), which may overlap a forward task
+  size_t ws_y1f[2] = {0, 0}, ws_yf[2][2] = {{0, 0}, {0, 0}};
   size_t slot_bytes = 0;
+  // re-computation: a resident micro-batch keeps only its input (and targets); the activations of
+  // the task being run live in one of two buffers of act_bytes (0: forward tasks, 1: backward tasks)
+  bool recompute = false;
+  size_t act_bytes = 0, st_x = 0, st_aux = 0, ws_act[2] = {0, 0}, ws_ydummy = 0;
   // workspace (bytes)
   // buffers the side stream reads exist twice (layers alternate between the sets)
   size_t ws_dx[2] = {0, 0}, ws_dz2[2] = {0, 0}, ws_du[2] = {0, 0}, ws_dy1 = 0, ws_dz1[2] = {0, 0}, ws_dctx = 0,
@@ -147,14 +154,25 @@ void build_layout(const stage_config& c, Layout& L) {
     L.sh_rows = stake(NP * 4); L.sh_tgt = stake(NP * 4); L.sh_r = stake(NP * H * E); L.sh_gl = stake(NP * H * E);
     L.sh_glp = stake(NP * H * E); L.sh_st = stake(2 * NP * 4); L.sh_t = stake(NP * H * E); L.sh_dz = stake(NP * VP * E);
   }
-  L.slot_bytes = so;
+  L.act_bytes = so;
+  L.recompute = (c.flags & STAGE_FLAG_RECOMPUTE) != 0;
+  if (L.recompute) {
+    size_t st = 0;
+    L.st_x = st; st += align_up(c.has_embedding ? T * 4 : U);
+    L.st_aux = st; st += c.has_mlm_head ? align_up(T * 4) : 0;
+    L.slot_bytes = st;
+  } else {
+    L.slot_bytes = so;
+  }
 
   size_t wo = 0;
   auto wtake = [&](size_t bytes) { size_t o = wo; wo += align_up(bytes); return o; };
   L.ws_dx[0] = wtake(U); L.ws_dx[1] = wtake(U); L.ws_dy1 = wtake(U); L.ws_dctx = wtake(U);
   L.ws_delta = wtake((size_t)c.micro_batch * c.n_heads * c.seq * 4);
   if (c.dtype == STAGE_DTYPE_BF16) {
-    L.ws_y1f = wtake(T * H * 4); L.ws_yf[0] = wtake(T * H * 4); L.ws_yf[1] = wtake(T * H * 4);
+    for (int fs = 0; fs < (L.recompute ? 2 : 1); ++fs) {
+      L.ws_y1f[fs] = wtake(T * H * 4); L.ws_yf[fs][0] = wtake(T * H * 4); L.ws_yf[fs][1] = wtake(T * H * 4);
+    }
   }
   const size_t ln_part = ((T + 7) / 8) * 3 * H * 4, cs_rows = (T + 63) / 64;
   for (int p = 0; p < 2; ++p) {
@@ -168,9 +186,13 @@ void build_layout(const stage_config& c, Layout& L) {
     L.wh_dgl = wtake(NP * H * E); L.wh_dh = wtake(NP * H * E); L.wh_dr = wtake(NP * H * E); L.wh_dyfull = wtake(U);
     size_t lp = ((NP + 7) / 8) * 3 * H * 4, cp = ((NP + 63) / 64) * VP * 4;
     L.wh_part = wtake(lp > cp ? lp : cp); L.wh_info = wtake(16);
+    if (L.recompute) { L.wh_logits2 = wtake(NP * VP * 4); L.wh_rowloss2 = wtake(NP * 4); L.wh_info2 = wtake(16); }
   }
   if (c.has_embedding) {
     L.we_dx0 = wtake(U); L.we_de = wtake(U); L.we_part = wtake(ln_part);
+  }
+  if (L.recompute) {
+    L.ws_act[0] = wtake(L.act_bytes); L.ws_act[1] = wtake(L.act_bytes); L.ws_ydummy = wtake(U);
   }
   L.workspace_bytes = wo;
 
@@ -181,7 +203,7 @@ void build_layout(const stage_config& c, Layout& L) {
   L.arena_bytes = L.arena_ws + L.workspace_bytes;
 }
 
-struct ProfEvent { hipEvent_t a, b; int cls; double flops; };
+struct ProfEvent { hipEvent_t a, b; int cls; double flops; int lane; };
 
 }  // namespace
 
@@ -250,7 +272,7 @@ struct dapple_stage {
         events.push_back(e);
       }
       pe = &events[events_used++];
-      pe->cls = cls; pe->flops = flops;
+      pe->cls = cls; pe->flops = flops; pe->lane = stream == st ? 0 : (stream == side ? 1 : 2);
       (void)hipEventRecord(pe->a, stream);
     }
     hipError_t e = fn(stream);
@@ -270,16 +292,16 @@ struct dapple_stage {
     return run_on(on_side ? side : cur, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); });
   }
 
-  int forward(int s, const void* x, void* y, const void* aux);
-  int backward(int s, const void* dy, void* dx);
+  // sl: where the task's activations live; fs: forward workspace set
+  int forward(char* sl, int fs, const void* x, void* y, const void* aux);
+  int backward(char* sl, const void* dy, void* dx);
 };
 
 #define TRY(expr) do { int rc_ = (expr); if (rc_ != STAGE_OK) return rc_; } while (0)
 
-int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
+int dapple_stage::forward(char* sl, int fs, const void* x, void* y, const void* aux) {
   const int H = cfg.hidden, F = cfg.ffn, T = cfg.micro_batch * cfg.seq;
   const size_t U = (size_t)T * H * E();
-  char* sl = slot(s);
   (void)aux;
   const char* xin = sl + L.slot_x0;
   // bf16 stages keep the residual stream unrounded: the pre-LayerNorm sums z1, z2 and the copy
@@ -288,7 +310,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
   const void* resid = xin;            // residual input of the next attention block
   bool resid_f32 = false;
   if (cfg.has_embedding) {
-    resid = mixed ? (const void*)ws(L.ws_yf[1]) : (const void*)xin;
+    resid = mixed ? (const void*)ws(L.ws_yf[fs][1]) : (const void*)xin;
     resid_f32 = mixed;
     // x = LN(E_w[id] + E_p[pos]); the ids and the pre-LN sum are kept for the backward
     int32_t* ids = (int32_t*)(sl + L.slot_ids);
@@ -298,7 +320,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
       return launch_embed_gather(dt, ids, w(L.embEw), w(L.embEp), esum, T, cfg.seq, H, cfg.vocab, q);
     }));
     TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) {
-      return launch_ln_fwd(dt, esum, false, w(L.embG), w(L.embB), sl + L.slot_x0, mixed ? (float*)ws(L.ws_yf[1]) : nullptr,
+      return launch_ln_fwd(dt, esum, false, w(L.embG), w(L.embB), sl + L.slot_x0, mixed ? (float*)ws(L.ws_yf[fs][1]) : nullptr,
                            (float*)(sl + L.slot_embst), T, H, cfg.ln_eps, q);
     }));
   } else {
@@ -333,7 +355,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
       ga.epi = EPI_BIAS | EPI_ADD | (mixed ? EPI_OUT32 : 0) | (resid_f32 ? EPI_AUX32 : 0);
       TRY(gemm(KC_GEMM_FWD, ga));
     }
-    float* y1f = mixed ? (float*)ws(L.ws_y1f) : nullptr;
+    float* y1f = mixed ? (float*)ws(L.ws_y1f[fs]) : nullptr;
     TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) {
       return launch_ln_fwd(dt, z1, mixed, w(p.ln1g), w(p.ln1b), y1, y1f, st1, T, H, cfg.ln_eps, q);
     }));
@@ -350,7 +372,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
       ga.K = F; ga.epi = EPI_BIAS | EPI_ADD | (mixed ? EPI_OUT32 | EPI_AUX32 : 0);
       TRY(gemm(KC_GEMM_FWD, ga));
     }
-    float* yf = (mixed && l + 1 < cfg.n_layers) ? (float*)ws(L.ws_yf[l & 1]) : nullptr;
+    float* yf = (mixed && l + 1 < cfg.n_layers) ? (float*)ws(L.ws_yf[fs][l & 1]) : nullptr;
     TRY(run(KC_LN_FWD, 0, [&](hipStream_t q) {
       return launch_ln_fwd(dt, z2, mixed, w(p.ln2g), w(p.ln2b), yout, yf, st2, T, H, cfg.ln_eps, q);
     }));
@@ -362,9 +384,9 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
     // gather the predicted rows, t = LN(GELU(r Wt + bt)), z = t E_out^T (+ b_out inside the
     // cross-entropy kernel), loss -> y[0]; dz is kept in the slot for the backward
     const int NP = L.NP, VP = L.VP, V = cfg.vocab;
-    int32_t *rows_idx = (int32_t*)(sl + L.sh_rows), *tgt = (int32_t*)(sl + L.sh_tgt), *info = (int32_t*)ws(L.wh_info);
+    int32_t *rows_idx = (int32_t*)(sl + L.sh_rows), *tgt = (int32_t*)(sl + L.sh_tgt), *info = (int32_t*)ws(fs ? L.wh_info2 : L.wh_info);
     char *r = sl + L.sh_r, *gl = sl + L.sh_gl, *glp = sl + L.sh_glp, *t = sl + L.sh_t, *dz = sl + L.sh_dz;
-    float *hst = (float*)(sl + L.sh_st), *logits = (float*)ws(L.wh_logits), *rowloss = (float*)ws(L.wh_rowloss);
+    float *hst = (float*)(sl + L.sh_st), *logits = (float*)ws(fs ? L.wh_logits2 : L.wh_logits), *rowloss = (float*)ws(fs ? L.wh_rowloss2 : L.wh_rowloss);
     const int cap = cfg.mlm_max_rows > 0 && cfg.mlm_max_rows < T ? cfg.mlm_max_rows : T;
     TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_mlm_compact((const int32_t*)aux, T, cap, NP, V, rows_idx, tgt, info, q); }));
     TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_gather_rows(dt, xin, rows_idx, r, NP, H, T, q); }));
@@ -388,7 +410,7 @@ int dapple_stage::forward(int s, const void* x, void* y, const void* aux) {
   return STAGE_OK;
 }
 
-int dapple_stage::backward(int s, const void* dy, void* dx) {
+int dapple_stage::backward(char* sl, const void* dy, void* dx) {
   // Two streams.  The caller's stream runs the chain that produces dx (LayerNorm backward,
   // data-gradient products, attention backward): it is the critical path.  Everything that only
   // feeds the gradient accumulators (weight-gradient products, bias column sums, LayerNorm
@@ -397,7 +419,6 @@ int dapple_stage::backward(int s, const void* dy, void* dx) {
   // side stream in program order: the result does not depend on how the two streams interleave.
   const int H = cfg.hidden, F = cfg.ffn, T = cfg.micro_batch * cfg.seq;
   const size_t U = (size_t)T * H * E();
-  char* sl = slot(s);
   char *dy1 = ws(L.ws_dy1), *dctx = ws(L.ws_dctx);
   float* delta = (float*)ws(L.ws_delta);
   const char* dyin = (const char*)dy;
@@ -678,6 +699,8 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
   int rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->grads, h->L.grad_bytes, q); });
   if (rc == STAGE_OK && cfg->has_mlm_head)
     rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->ws(h->L.wh_info), 16, q); });
+    if (rc == STAGE_OK && h->L.recompute)
+      rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->ws(h->L.wh_info2), 16, q); });
   if (rc != STAGE_OK) { delete h; return rc; }
   *out = h;
   return STAGE_OK;
@@ -715,7 +738,22 @@ int stage_fwd(stage_handle h, int mb, const void* x_dev, void* y_dev, const void
   if (find_slot(h, mb) >= 0) return fail(STAGE_E_DUP_MB, "micro-batch %d is already resident", mb);
   int s = find_slot(h, -1);
   if (s < 0) return fail(STAGE_E_NO_SLOT, "all %d activation slots are in use", h->cfg.max_slots);
-  TRY(h->forward(s, x_dev, y_dev, aux_dev));
+  if (h->L.recompute && !h->dry) {
+    // keep only what the forward cannot be re-run without: the input (token ids on a first stage)
+    // and the targets; the activations go to the forward tasks' buffer and are dropped
+    char* stash = h->slot(s);
+    const Layout& L = h->L;
+    const size_t xb = h->cfg.has_embedding ? (size_t)h->cfg.micro_batch * h->cfg.seq * 4
+                                            : (size_t)h->cfg.micro_batch * h->cfg.seq * h->cfg.hidden * h->E();
+    TRY(h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_copy(stash + L.st_x, x_dev, xb, q); }));
+    if (h->cfg.has_mlm_head)
+      TRY(h->run(KC_COPY, 0, [&](hipStream_t q) {
+        return launch_copy(stash + L.st_aux, aux_dev, (size_t)h->cfg.micro_batch * h->cfg.seq * 4, q);
+      }));
+    TRY(h->forward(h->ws(L.ws_act[0]), 0, x_dev, y_dev, aux_dev));
+  } else {
+    TRY(h->forward(h->slot(s), 0, x_dev, y_dev, aux_dev));
+  }
   h->slot_of_mb[s] = mb;
   ++h->live;
   if (h->live > h->peak_live) h->peak_live = h->live;
@@ -729,7 +767,15 @@ int stage_bwd(stage_handle h, int mb, const void* dy_dev, void* dx_dev) {
   if (!h->dry && !h->cfg.has_embedding && !dx_dev) return fail(STAGE_E_NULL, "dx_dev must not be NULL");
   int s = mb < 0 ? -1 : find_slot(h, mb);
   if (s < 0) return fail(STAGE_E_NOT_RESIDENT, "micro-batch %d has no live forward", mb);
-  TRY(h->backward(s, dy_dev, dx_dev));
+  if (h->L.recompute && !h->dry) {
+    // re-run the forward from the kept input into the backward tasks' buffer, then go backward
+    const Layout& L = h->L;
+    char *stash = h->slot(s), *act = h->ws(L.ws_act[1]);
+    TRY(h->forward(act, 1, stash + L.st_x, h->ws(L.ws_ydummy), h->cfg.has_mlm_head ? stash + L.st_aux : nullptr));
+    TRY(h->backward(act, dy_dev, dx_dev));
+  } else {
+    TRY(h->backward(h->slot(s), dy_dev, dx_dev));
+  }
   h->slot_of_mb[s] = -1;   // released after its backward: the next injected micro-batch reuses it
   --h->live;
   ++h->bwd_tasks;
@@ -778,7 +824,7 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
   // themselves and backwards among themselves in list order (which fixes the order of every
   // gradient accumulation).  The early-backward order needs no more than that; the other orders
   // are run strictly as listed (a backward waits for every forward listed before it).
-  const bool lanes = !h->dry && !h->profiling && !h->serial;
+  const bool lanes = !h->dry && (!h->profiling || getenv("DAPPLE_TIMELINE")) && !h->serial;
   const bool strict = order != STAGE_ORDER_EARLY_BACKWARD;
   std::vector<char> b_pending(h->cfg.max_slots, 0);
   int last_f_slot = -1;
@@ -841,7 +887,7 @@ int stage_zero_grads(stage_handle h) {
 int stage_stats(stage_handle h, stage_stats_t* out) {
   if (!h || !out) return fail(STAGE_E_NULL, "handle and out must not be NULL");
   out->slot_bytes = h->L.slot_bytes;
-  out->peak_activation_bytes = (uint64_t)h->peak_live * h->L.slot_bytes;
+  out->peak_activation_bytes = (uint64_t)h->peak_live * h->L.slot_bytes + (h->L.recompute ? 2 * (uint64_t)h->L.act_bytes : 0);
   out->live_slots = h->live;
   out->peak_live_slots = h->peak_live;
   out->fwd_tasks = h->fwd_tasks;
@@ -870,7 +916,22 @@ int stage_profile_read(stage_handle h, int n, uint64_t* launches, double* ms, do
   if (!h || !launches || !ms || !flops) return fail(STAGE_E_NULL, "arguments must not be NULL");
   if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
+  if (!h->dry && h->fwd && hipStreamSynchronize(h->fwd) != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed");
   for (int i = 0; i < n; ++i) { launches[i] = 0; ms[i] = 0; flops[i] = 0; }
+  if (const char* path = getenv("DAPPLE_TIMELINE")) {
+    // debugging aid: every launch of the profiled steps as "class,lane,start_ms,end_ms" (lane 0 = caller's
+    // stream, 1 = side, 2 = forward), times relative to the first launch
+    if (FILE* f = fopen(path, "w")) {
+      for (size_t i = 0; i < h->events_used; ++i) {
+        const ProfEvent& e = h->events[i];
+        float t0 = 0.f, t1 = 0.f;
+        (void)hipEventElapsedTime(&t0, h->events[0].a, e.a);
+        (void)hipEventElapsedTime(&t1, h->events[0].a, e.b);
+        fprintf(f, "%s,%d,%.4f,%.4f\n", kClassNames[e.cls], e.lane, t0, t1);
+      }
+      fclose(f);
+    }
+  }
   for (size_t i = 0; i < h->events_used; ++i) {
     const ProfEvent& e = h->events[i];
     if (e.cls >= n) continue;
@@ -893,6 +954,8 @@ int stage_sync(stage_handle h) {
   if (h->cfg.has_mlm_head) {
     int32_t info[2] = {0, 0};
     if (hipMemcpy(info, h->ws(h->L.wh_info), 8, hipMemcpyDeviceToHost) != hipSuccess)
+      return fail(STAGE_E_DEVICE, "hipMemcpy failed");
+    if (h->L.recompute && !info[1] && hipMemcpy(info, h->ws(h->L.wh_info2), 8, hipMemcpyDeviceToHost) != hipSuccess)
       return fail(STAGE_E_DEVICE, "hipMemcpy failed");
     if (info[1]) return fail(STAGE_E_CONFIG, "a micro-batch predicted more rows than mlm_max_rows; the surplus was dropped");
   }

@@ -16,12 +16,12 @@ def to_np(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def c_config(cfg: I.StageConfig, max_slots, loss_scale=1.0):
+def c_config(cfg: I.StageConfig, max_slots, loss_scale=1.0, flags=0):
     import math
     return B.make_config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, max_slots,
                          B.DTYPE_BF16 if cfg.dtype == "bf16" else B.DTYPE_F32, cfg.has_embedding,
                          cfg.has_mlm_head, cfg.vocab if (cfg.has_embedding or cfg.has_mlm_head) else 0,
-                         cfg.max_pos if cfg.has_embedding else 0, 0, cfg.ln_eps, loss_scale,
+                         cfg.max_pos if cfg.has_embedding else 0, flags, cfg.ln_eps, loss_scale,
                          math.ceil(0.15 * cfg.tokens) if cfg.has_mlm_head else 0)
 
 
@@ -37,11 +37,11 @@ def make_inputs(cfg, seed, M=None):
     return theta, mbs
 
 
-def run_gpu(cfg, theta, mbs, M, K, order, max_slots=None, loss_scale=1.0, explicit_ops=None):
+def run_gpu(cfg, theta, mbs, M, K, order, max_slots=None, loss_scale=1.0, explicit_ops=None, flags=0):
     """Run one iteration on the GPU; returns dict(ys, dxs, grads, stats) as numpy float64."""
     import torch
     slots = max_slots if max_slots is not None else (M if order == B.ORDER_GPIPE else min(K, M))
-    r = B.StageRunner(c_config(cfg, slots, loss_scale), theta)
+    r = B.StageRunner(c_config(cfg, slots, loss_scale, flags), theta)
     try:
         T, H = cfg.tokens, cfg.hidden
         if cfg.has_embedding:

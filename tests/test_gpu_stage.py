@@ -157,3 +157,41 @@ def test_bert_large_shaped_stage_full_size():
     cfg = I.CONFIGS["bert_large"]
     worst = check_config(cfg, cfg.M, cfg.K, TOL_BF16)
     print("bert_large worst:", worst)
+
+
+# ---- re-computation (section VI-E, Table VI "+ RC"): same numbers, a fraction of the memory
+def _recompute_case(cfg, M, K, order):
+    theta, mbs = make_inputs(cfg, SEED, M)
+    a = run_gpu(cfg, theta, mbs, M, K, order)
+    b = run_gpu(cfg, theta, mbs, M, K, order, flags=B.FLAG_RECOMPUTE)
+    assert np.array_equal(a["grads"], b["grads"])          # the same kernels on the same values
+    for m in range(M):
+        assert np.array_equal(a["ys"][m], b["ys"][m])
+        if a["dxs"] is not None:
+            assert np.array_equal(a["dxs"][m], b["dxs"][m])
+    return a["stats"], b["stats"]
+
+
+def test_recompute_matches_stored_activations_bitwise_and_keeps_only_the_boundary():
+    cfg = I.StageConfig(3, 256, 4, 512, 128, 2, 5, 2, "bf16")
+    for order in (B.ORDER_EARLY_BACKWARD, B.ORDER_GPIPE):
+        full, rc = _recompute_case(cfg, 5, 2, order)
+        T, H = cfg.tokens, cfg.hidden
+        assert rc["slot_bytes"] == T * H * 2                # the stage input, nothing else
+        live = 2 if order == B.ORDER_EARLY_BACKWARD else 5
+        assert rc["peak_live"] == full["peak_live"] == live
+        # K boundary tensors + one activation buffer per lane, against K full slots
+        assert rc["peak_bytes"] == live * rc["slot_bytes"] + 2 * full["slot_bytes"]
+    # and against the oracle
+    theta, mbs = make_inputs(cfg, SEED, 5)
+    st, ref = run_oracle(cfg, theta, mbs, 5, 2)
+    g = run_gpu(cfg, theta, mbs, 5, 2, B.ORDER_EARLY_BACKWARD, flags=B.FLAG_RECOMPUTE)
+    compare(cfg, st, ref, g, TOL_BF16, 5)
+
+
+def test_recompute_fp32_first_and_last_stage():
+    _recompute_case(I.CONFIGS["tiny"], 4, 2, B.ORDER_EARLY_BACKWARD)
+    emb = I.StageConfig(2, 128, 2, 256, 64, 2, 3, 2, "bf16", has_embedding=True, vocab=512, max_pos=64)
+    _recompute_case(emb, 3, 2, B.ORDER_EARLY_BACKWARD)
+    head = I.StageConfig(2, 128, 2, 256, 64, 2, 3, 2, "bf16", has_mlm_head=True, vocab=520)
+    _recompute_case(head, 3, 2, B.ORDER_EARLY_BACKWARD)

@@ -64,6 +64,23 @@ def test_config_errors():
     assert e.value.code == B.STAGE_E_ARENA_SMALL
 
 
+def test_recompute_keeps_only_the_boundary_per_slot():
+    # section VI-E: with re-computation a resident micro-batch keeps its input only; the two
+    # activation buffers (forward tasks, backward tasks) do not scale with the slots
+    full = B.stage_query_sizes(dry(2))
+    rc2 = B.stage_query_sizes(dry(2, flags=B.FLAG_DRY_RUN | B.FLAG_RECOMPUTE))
+    rc8 = B.stage_query_sizes(dry(8, flags=B.FLAG_DRY_RUN | B.FLAG_RECOMPUTE))
+    T, H = 2 * 16, 64
+    assert rc2.slot_bytes == T * H * 4 < full.slot_bytes
+    assert rc8.arena_bytes - rc2.arena_bytes == 6 * rc2.slot_bytes
+    assert rc2.workspace_bytes >= full.workspace_bytes + 2 * full.slot_bytes
+    # first stage: token ids; last stage: input and targets
+    emb = B.stage_query_sizes(dry(2, flags=B.FLAG_DRY_RUN | B.FLAG_RECOMPUTE, has_embedding=1, vocab=100, max_pos=16))
+    assert emb.slot_bytes == 256          # T int32 ids, rounded up to the 256-byte granule
+    head = B.stage_query_sizes(dry(2, flags=B.FLAG_DRY_RUN | B.FLAG_RECOMPUTE, has_mlm_head=1, vocab=100))
+    assert head.slot_bytes == T * H * 4 + 256
+
+
 def test_sizes_scale_with_slots_only():
     a, b = B.stage_query_sizes(dry(2)), B.stage_query_sizes(dry(4))
     assert a.slot_bytes == b.slot_bytes and a.grad_bytes == b.grad_bytes
