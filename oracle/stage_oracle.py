@@ -391,3 +391,26 @@ def full_batch(stage: Stage, xs, dys=None, targets=None):
     DY = None if dys is None else np.concatenate([np.asarray(d) for d in dys], axis=0)
     dX, G = stage.backward(DY, cache)
     return dict(y=Y, dx=dX, grads=G)
+
+
+# ---------------------------------------------------------------- synchronous weights update
+def adam_apply(theta, m, v, G, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, grad_scale=1.0):
+    """The Apply of section V-B-3 for the optimizer the paper trains BERT-48 with (Adam, section
+    VI-A): one update of the weights theta from the gradients G accumulated over the iteration's
+    micro-batches, averaged by grad_scale (1 / number of samples or micro-batches, the caller's
+    choice).  Adam as its authors state it (Kingma & Ba, Algorithm 1), step counted from 1:
+
+        g = grad_scale * G
+        m <- beta1 m + (1 - beta1) g          v <- beta2 v + (1 - beta2) g^2
+        theta <- theta - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+
+    Returns the new (theta, m, v) as float64 arrays; the inputs are not modified.
+    Pins (tests/test_oracle_adam.py): torch.optim.Adam in float64 over several steps; the closed
+    form of the first step (|update| = lr |g| / (|g| + eps)); a zero gradient leaves theta alone."""
+    theta, m, v, G = (np.asarray(a, dtype=np.float64) for a in (theta, m, v, G))
+    g = grad_scale * G
+    m1 = beta1 * m + (1.0 - beta1) * g
+    v1 = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m1 / (1.0 - beta1 ** step)
+    vhat = v1 / (1.0 - beta2 ** step)
+    return theta - lr * mhat / (np.sqrt(vhat) + eps), m1, v1
