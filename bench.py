@@ -149,6 +149,20 @@ def main():
     classes = {k: {"launches_per_step": v["launches"] / prof_steps, "ms_per_step": v["ms"] / prof_steps,
                    "tflops": (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["ms"] > 0 and v["flops"] > 0 else None}
                for k, v in prof.items() if v["launches"]}
+    # the Apply step that closes a training iteration: one fused Adam pass over the stage's parameters
+    # (reads g, w, m, v in fp32; writes w, m, v, the weight in the stage's dtype and the zeroed g)
+    r.init_adam()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(2):
+        r.apply_adam(1e-4, grad_scale=1.0 / (M * cfg.micro_batch), zero_grads=True)
+    e0.record()
+    n_apply = 10
+    for _ in range(n_apply):
+        r.apply_adam(1e-4, grad_scale=1.0 / (M * cfg.micro_batch), zero_grads=True)
+    e1.record()
+    torch.cuda.synchronize()
+    apply_ms = e0.elapsed_time(e1) / n_apply
+    apply_bytes = r.sizes.n_params * (16 + 12 + 4 + (2 if cfg.dtype == "bf16" else 4))
     r.close()
 
     sec = results["early_backward"]
@@ -178,6 +192,8 @@ def main():
                       "throughput_vs_stored": sec / results["early_backward_recompute"],
                       "memory_vs_stored": peak_bytes["early_backward_recompute"] / peak_bytes["early_backward"],
                       "memory_vs_gpipe_order": peak_bytes["early_backward_recompute"] / peak_bytes["gpipe"]},
+        "apply_adam": {"ms": apply_ms, "params": int(r.sizes.n_params), "bytes": int(apply_bytes),
+                       "GB/s": apply_bytes / (apply_ms * 1e-3) / 1e9, "hbm_peak_frac": apply_bytes / (apply_ms * 1e-3) / 8e12},
         "kernel_classes": classes,
     }
     if not args.no_cpu_baseline:

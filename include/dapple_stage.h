@@ -162,6 +162,22 @@ int stage_run_schedule(stage_handle h, int M, int K, int order,
 int stage_grads(stage_handle h, void** grads_dev, uint64_t* n);
 int stage_zero_grads(stage_handle h);
 
+/* The Apply of the synchronous weights update (section V-B-3) with the optimizer the paper
+ * trains BERT-48 with (Adam, section VI-A; 16 bytes of fp32 state per parameter, Table VIII):
+ * one fused pass over all parameters of the stage, to be called after the iteration's tasks.
+ *   g = grad_scale * G (the averaging over the iteration's samples is the caller's choice),
+ *   m = beta1 m + (1-beta1) g,  v = beta2 v + (1-beta2) g^2,
+ *   master -= lr * (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps),  step >= 1,
+ *   weights = master rounded to the stage's dtype.
+ * weights_dev: the buffer given to stage_init (it is written here and nowhere else);
+ * master_dev, m_dev, v_dev: device fp32 [n_params], 16-byte aligned, owned by the caller
+ * (master initialised to the weights, moments to zero).  zero_grads != 0 also clears the
+ * accumulators in the same pass.  Fails with STAGE_E_BAD_ORDER while micro-batches are
+ * resident. */
+int stage_apply_adam(stage_handle h, void* weights_dev, float* master_dev, float* m_dev, float* v_dev,
+                     int step, float lr, float beta1, float beta2, float eps, float grad_scale,
+                     int zero_grads);
+
 int stage_stats(stage_handle h, stage_stats_t* out);
 int stage_reset_stats(stage_handle h);
 

@@ -65,6 +65,7 @@ SYMBOLS = {
     "stage_run_schedule": (_i, [_vp, _i, _i, _i, _pp, _pp, _pp, _pp, _pp, C.POINTER(C.c_int32), _i]),
     "stage_grads": (_i, [_vp, C.POINTER(_vp), C.POINTER(C.c_uint64)]),
     "stage_zero_grads": (_i, [_vp]),
+    "stage_apply_adam": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _f, _f, _f, _f, _f, _i]),
     "stage_stats": (_i, [_vp, C.POINTER(stage_stats_t)]),
     "stage_reset_stats": (_i, [_vp]),
     "stage_profile_enable": (_i, [_vp, _i]),
@@ -176,6 +177,12 @@ def stage_zero_grads(h):
     _check(load().stage_zero_grads(h))
 
 
+def stage_apply_adam(h, weights_ptr, master_ptr, m_ptr, v_ptr, step, lr, beta1=0.9, beta2=0.999, eps=1e-8,
+                     grad_scale=1.0, zero_grads=False):
+    _check(load().stage_apply_adam(h, weights_ptr, master_ptr, m_ptr, v_ptr, step, lr, beta1, beta2, eps,
+                                   grad_scale, int(zero_grads)))
+
+
 def stage_stats(h) -> stage_stats_t:
     out = stage_stats_t()
     _check(load().stage_stats(h, C.byref(out)))
@@ -271,6 +278,19 @@ class StageRunner:
         p, n = stage_grads(self.h)
         assert p == self.grads.data_ptr() and n == self.sizes.n_params
         self.T = cfg.micro_batch * cfg.seq
+
+    def init_adam(self):
+        """fp32 master copy of the weights and zeroed moments (the optimizer state is the caller's)."""
+        torch = self.torch
+        self.master = self.weights.to(torch.float32).clone().contiguous()
+        self.m = torch.zeros_like(self.master)
+        self.v = torch.zeros_like(self.master)
+        self.step = 0
+
+    def apply_adam(self, lr, beta1=0.9, beta2=0.999, eps=1e-8, grad_scale=1.0, zero_grads=False):
+        self.step += 1
+        stage_apply_adam(self.h, self.weights.data_ptr(), self.master.data_ptr(), self.m.data_ptr(),
+                         self.v.data_ptr(), self.step, lr, beta1, beta2, eps, grad_scale, zero_grads)
 
     def to_dev(self, a, dtype=None):
         t = self.torch.as_tensor(a)

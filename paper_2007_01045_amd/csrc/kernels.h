@@ -123,4 +123,11 @@ hipError_t launch_mlm_ce(Dtype dt, const float* logits, const void* bias, const 
                          hipStream_t st);
 hipError_t launch_mul(Dtype dt, const void* a, const void* b, void* c, long n, hipStream_t st);
 
+// ---------------------------------------------------------------- weight update
+// One Adam step over n parameters: g = grad_scale * G; m, v, w32 updated in fp32 (c1, c2: the
+// reciprocal bias corrections 1/(1-beta1^step), 1/(1-beta2^step)); w = w32 in the stage's dtype;
+// G is zeroed when zero_grads is set.  All fp32 pointers 16-byte aligned.
+hipError_t launch_adam(Dtype dt, float* G, float* w32, float* m, float* v, void* w, size_t n, float lr, float beta1,
+                       float beta2, float eps, float c1, float c2, float grad_scale, int zero_grads, hipStream_t st);
+
 }  // namespace dapple

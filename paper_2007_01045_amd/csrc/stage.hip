@@ -884,6 +884,24 @@ int stage_zero_grads(stage_handle h) {
   return h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->grads, h->L.grad_bytes, q); });
 }
 
+int stage_apply_adam(stage_handle h, void* weights_dev, float* master_dev, float* m_dev, float* v_dev, int step, float lr,
+                     float beta1, float beta2, float eps, float grad_scale, int zero_grads) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  if (step < 1) return fail(STAGE_E_CONFIG, "step counts from 1 (got %d)", step);
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps > 0.f))
+    return fail(STAGE_E_CONFIG, "beta1 and beta2 must lie in [0, 1) and eps must be positive");
+  if (h->live != 0) return fail(STAGE_E_BAD_ORDER, "%d micro-batches are still resident: the update belongs after the iteration", h->live);
+  if (h->dry) { ++h->launches; return STAGE_OK; }
+  if (!weights_dev || !master_dev || !m_dev || !v_dev) return fail(STAGE_E_NULL, "weights, master weights and both moments must not be NULL");
+  if (weights_dev != (const void*)h->W) return fail(STAGE_E_CONFIG, "weights_dev must be the weights buffer given to stage_init");
+  if (((uintptr_t)master_dev | (uintptr_t)m_dev | (uintptr_t)v_dev) % 16) return fail(STAGE_E_CONFIG, "fp32 state must be 16-byte aligned");
+  const double c1 = 1.0 / (1.0 - std::pow((double)beta1, step)), c2 = 1.0 / (1.0 - std::pow((double)beta2, step));
+  return h->run(KC_COPY, 0, [&](hipStream_t q) {
+    return launch_adam(h->dt, h->grads, master_dev, m_dev, v_dev, weights_dev, h->L.n_params, lr, beta1, beta2, eps,
+                       (float)c1, (float)c2, grad_scale, zero_grads, q);
+  });
+}
+
 int stage_stats(stage_handle h, stage_stats_t* out) {
   if (!h || !out) return fail(STAGE_E_NULL, "handle and out must not be NULL");
   out->slot_bytes = h->L.slot_bytes;
