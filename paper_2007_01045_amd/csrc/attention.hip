@@ -126,22 +126,20 @@ __device__ __forceinline__ int aswz(int r) {
 }
 
 // a 64 x 64 block in flight from global memory: 2 chunks of 16 bytes per thread (256 threads)
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 struct Block64 {
-  uint4 c[2];
+  // native vectors in named members: with the runtime's uint4 (a struct around a union) the
+  // compiler kept the block in scratch memory and waited for the loads at once
+  i32x4 c0, c1;
   __device__ __forceinline__ void load(const bf16* g, int ldg, int tid) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      int ch = tid + 256 * i;
-      c[i] = *(const uint4*)(g + (long)(ch >> 3) * ldg + (ch & 7) * 8);
-    }
+    c0 = *(const i32x4*)(g + (long)(tid >> 3) * ldg + (tid & 7) * 8);
+    c1 = *(const i32x4*)(g + (long)((tid + 256) >> 3) * ldg + (tid & 7) * 8);
   }
   __device__ __forceinline__ void store(bf16* S, int tid) const {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      int ch = tid + 256 * i;
-      int r = ch >> 3, kc = ch & 7;
-      *(uint4*)(S + r * AD + ((kc ^ aswz(r)) << 3)) = c[i];
-    }
+    int r = tid >> 3, kc = tid & 7;
+    *(i32x4*)(S + r * AD + ((kc ^ aswz(r)) << 3)) = c0;
+    r += 32;
+    *(i32x4*)(S + r * AD + ((kc ^ aswz(r)) << 3)) = c1;
   }
 };
 // operand fragment, contraction index contiguous in LDS: rows r0 + (lane&31), k = 16 kk + 8 (lane>>5) + e
@@ -216,23 +214,39 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnArgs a, float scale2) {
     kblk.store(Ks, tid);
     vblk.store(Vs, tid);
     __syncthreads();
-    if (kb + 1 < nkb) {
-      kblk.load(K + (long)(kb + 1) * 64 * a.H, a.H, tid);
-      vblk.load(V + (long)(kb + 1) * 64 * a.H, a.H, tid);
+    {  // unconditional: the last iteration fetches its own block again (harmless, and it keeps
+       // the in-flight block in registers instead of scratch)
+      const int nb = kb + 1 < nkb ? kb + 1 : kb;
+      kblk.load(K + (long)nb * 64 * a.H, a.H, tid);
+      vblk.load(V + (long)nb * 64 * a.H, a.H, tid);
     }
     float p[2][16];
     float mx = -INFINITY;
+    // All LDS reads of a phase are issued before its first MFMA (left to itself the compiler
+    // reuses one register set and waits for every read in turn): the 8 key fragments, then the
+    // 8 value fragments, which land while the softmax arithmetic runs.
+    bf16x8 kf[2][4], vf[4][2];
+#pragma unroll
+    for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) kf[kb2][kk] = frag_rows(Ks, kb2 * 32, kk, lane);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kb2 = 0; kb2 < 2; ++kb2) {
       f32x16 sa = zero16();  // rows: key 32 kb2 + 8 blk + 4 h + e, column: query
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) sa = MFMA(frag_rows(Ks, kb2 * 32, kk, lane), qf[kk], sa);
+      for (int kk = 0; kk < 4; ++kk) sa = MFMA(kf[kb2][kk], qf[kk], sa);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         p[kb2][v] = sa[v] * scale2;
         mx = fmaxf(mx, p[kb2][v]);
       }
     }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int db = 0; db < 2; ++db) vf[ks][db] = frag_cols(Vs, db * 32, ks * 16, lane);
+    __builtin_amdgcn_sched_barrier(0);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     float mn = fmaxf(m, mx);
     float alpha = exp2f(m - mn);
@@ -255,7 +269,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnArgs a, float scale2) {
     for (int ks = 0; ks < 4; ++ks) {
       bf16x8 pf = acc_to_operand(p[ks >> 1], ks & 1);
 #pragma unroll
-      for (int db = 0; db < 2; ++db) o[db] = MFMA(frag_cols(Vs, db * 32, ks * 16, lane), pf, o[db]);
+      for (int db = 0; db < 2; ++db) o[db] = MFMA(vf[ks][db], pf, o[db]);
     }
   }
   if (qok) {
@@ -313,24 +327,46 @@ __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, 
     if (tid < 64) Ls[tid] = stat;
     else if (tid < 128) Ds[tid - 64] = stat;
     __syncthreads();
-    if (qb + 1 < nqb) {
-      qblk.load(Q + (long)(qb + 1) * 64 * a.H, a.H, tid);
-      gblk.load(G + (long)(qb + 1) * 64 * a.H, a.H, tid);
-      stat = tid < 64 ? lse[(qb + 1) * 64 + tid] : (tid < 128 ? dl[(qb + 1) * 64 + tid - 64] : 0.f);
+    {  // unconditional (the last iteration fetches its own block again): keeps the block in registers
+      const int nb = qb + 1 < nqb ? qb + 1 : qb;
+      qblk.load(Q + (long)nb * 64 * a.H, a.H, tid);
+      gblk.load(G + (long)nb * 64 * a.H, a.H, tid);
+      stat = tid < 64 ? lse[nb * 64 + tid] : (tid < 128 ? dl[nb * 64 + tid - 64] : 0.f);
     }
 #pragma unroll
     for (int qb2 = 0; qb2 < 2; ++qb2) {
+      // every LDS read of a phase before its first MFMA (see attn_fwd_mfma)
+      bf16x8 qf[4], gf[4], gc[2][2], qc[2][2];
+      float4 L4s[4], D4s[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        qf[kk] = frag_rows(Qs, qb2 * 32, kk, lane);
+        gf[kk] = frag_rows(Gs, qb2 * 32, kk, lane);
+      }
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk) {
+        L4s[blk] = *(const float4*)(Ls + qb2 * 32 + 8 * blk + 4 * h);
+        D4s[blk] = *(const float4*)(Ds + qb2 * 32 + 8 * blk + 4 * h);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       f32x16 sa = zero16(), dp = zero16();  // rows: query 32 qb2 + 8 blk + 4 h + e, column: key
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        sa = MFMA(frag_rows(Qs, qb2 * 32, kk, lane), kf[kk], sa);
-        dp = MFMA(frag_rows(Gs, qb2 * 32, kk, lane), vf[kk], dp);
+        sa = MFMA(qf[kk], kf[kk], sa);
+        dp = MFMA(gf[kk], vf[kk], dp);
       }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          gc[ks][db] = frag_cols(Gs, db * 32, qb2 * 32 + ks * 16, lane);
+          qc[ks][db] = frag_cols(Qs, db * 32, qb2 * 32 + ks * 16, lane);
+        }
+      __builtin_amdgcn_sched_barrier(0);
       float p[16], ds[16];
 #pragma unroll
       for (int blk = 0; blk < 4; ++blk) {
-        float4 L4 = *(const float4*)(Ls + qb2 * 32 + 8 * blk + 4 * h);
-        float4 D4 = *(const float4*)(Ds + qb2 * 32 + 8 * blk + 4 * h);
+        float4 L4 = L4s[blk], D4 = D4s[blk];
         float Lv[4] = {L4.x, L4.y, L4.z, L4.w}, Dv[4] = {D4.x, D4.y, D4.z, D4.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -344,8 +380,8 @@ __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, 
         bf16x8 pf = acc_to_operand(p, ks), dsf = acc_to_operand(ds, ks);
 #pragma unroll
         for (int db = 0; db < 2; ++db) {
-          dv[db] = MFMA(frag_cols(Gs, db * 32, qb2 * 32 + ks * 16, lane), pf, dv[db]);
-          dk[db] = MFMA(frag_cols(Qs, db * 32, qb2 * 32 + ks * 16, lane), dsf, dk[db]);
+          dv[db] = MFMA(gc[ks][db], pf, dv[db]);
+          dk[db] = MFMA(qc[ks][db], dsf, dk[db]);
         }
       }
     }
@@ -418,18 +454,33 @@ __global__ __launch_bounds__(256) void attn_dq_mfma(AttnArgs a, float scale2, fl
     kblk.store(Ks, tid);
     vblk.store(Vs, tid);
     __syncthreads();
-    if (kb + 1 < nkb) {
-      kblk.load(K + (long)(kb + 1) * 64 * a.H, a.H, tid);
-      vblk.load(V + (long)(kb + 1) * 64 * a.H, a.H, tid);
+    {  // unconditional: the last iteration fetches its own block again (harmless, and it keeps
+       // the in-flight block in registers instead of scratch)
+      const int nb = kb + 1 < nkb ? kb + 1 : kb;
+      kblk.load(K + (long)nb * 64 * a.H, a.H, tid);
+      vblk.load(V + (long)nb * 64 * a.H, a.H, tid);
     }
 #pragma unroll
     for (int kb2 = 0; kb2 < 2; ++kb2) {
+      // every LDS read of a phase before its first MFMA (see attn_fwd_mfma)
+      bf16x8 kr[4], vr[4], kc[2][2];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        kr[kk] = frag_rows(Ks, kb2 * 32, kk, lane);
+        vr[kk] = frag_rows(Vs, kb2 * 32, kk, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       f32x16 sa = zero16(), dp = zero16();  // rows: key 32 kb2 + 8 blk + 4 h + e, column: query
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        sa = MFMA(frag_rows(Ks, kb2 * 32, kk, lane), qf[kk], sa);
-        dp = MFMA(frag_rows(Vs, kb2 * 32, kk, lane), gf[kk], dp);
+        sa = MFMA(kr[kk], qf[kk], sa);
+        dp = MFMA(vr[kk], gf[kk], dp);
       }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) kc[ks][db] = frag_cols(Ks, db * 32, kb2 * 32 + ks * 16, lane);
+      __builtin_amdgcn_sched_barrier(0);
       float ds[16];
 #pragma unroll
       for (int v = 0; v < 16; ++v) ds[v] = exp2f(sa[v] * scale2 - Lq) * (dp[v] - Dq);
@@ -437,8 +488,7 @@ __global__ __launch_bounds__(256) void attn_dq_mfma(AttnArgs a, float scale2, fl
       for (int ks = 0; ks < 2; ++ks) {
         bf16x8 dsf = acc_to_operand(ds, ks);
 #pragma unroll
-        for (int db = 0; db < 2; ++db)
-          dq[db] = MFMA(frag_cols(Ks, db * 32, kb2 * 32 + ks * 16, lane), dsf, dq[db]);
+        for (int db = 0; db < 2; ++db) dq[db] = MFMA(kc[ks][db], dsf, dq[db]);
       }
     }
   }

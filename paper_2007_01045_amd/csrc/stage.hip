@@ -207,6 +207,8 @@ struct ProfEvent { hipEvent_t a, b; int cls; double flops; int lane; };
 
 }  // namespace
 
+static int envi(const char* name) { const char* e = getenv(name); return e ? atoi(e) : 0; }
+
 struct dapple_stage {
   stage_config cfg;
   Layout L;
@@ -289,7 +291,18 @@ struct dapple_stage {
     if (g.n_valid == 0) g.n_valid = g.N;
     if (g.batch == 0) g.batch = 1;
     double flops = 2.0 * g.M * g.N * (double)g.K * g.batch;
-    return run_on(on_side ? side : cur, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); });
+    hipStream_t s_ = on_side ? side : cur;
+    {  // tuning: DAPPLE_TILE_<lane>_<BIG|MID|SMALL> picks the tile configuration per lane and size class
+      static const int tab[3][3] = {
+          {envi("DAPPLE_TILE_MAIN_BIG"), envi("DAPPLE_TILE_MAIN_MID"), envi("DAPPLE_TILE_MAIN_SMALL")},
+          {envi("DAPPLE_TILE_SIDE_BIG"), envi("DAPPLE_TILE_SIDE_MID"), envi("DAPPLE_TILE_SIDE_SMALL")},
+          {envi("DAPPLE_TILE_FWD_BIG"), envi("DAPPLE_TILE_FWD_MID"), envi("DAPPLE_TILE_FWD_SMALL")}};
+      const int lane = s_ == st ? 0 : (s_ == side ? 1 : 2);
+      const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
+      const int cl = t128 > 256 ? 0 : (t128 >= 192 ? 1 : 2);
+      if (!g.tile) g.tile = tab[lane][cl];
+    }
+    return run_on(s_, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); });
   }
 
   // sl: where the task's activations live; fs: forward workspace set
