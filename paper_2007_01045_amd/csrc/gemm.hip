@@ -408,8 +408,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   const int epi = g.epi;
   // one 32-row block; the block index is a compile-time constant so that the
   // accumulators are always addressed statically (they must stay in registers)
-  auto store_block = [&](auto I) {
+  auto store_block = [&](auto I, auto FULLC) {
     constexpr int i = decltype(I)::value;
+    // FULL: the whole tile lies inside the matrix, no element needs a bounds test
+    constexpr bool FULL = decltype(FULLC)::value;
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -436,7 +438,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
         if (epi & EPI_BIAS) {
 #pragma unroll
           for (int u = 0; u < HB; ++u)
-            if (cols[u] < g.N) {
+            if (FULL || cols[u] < g.N) {
               bf16x4 bv = *(const bf16x4*)((const bf16*)g.bias + zbias + cols[u]);
               t[u].x += (float)bv[0]; t[u].y += (float)bv[1]; t[u].z += (float)bv[2]; t[u].w += (float)bv[3];
             }
@@ -445,7 +447,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
           float4 xv[HB];
 #pragma unroll
           for (int u = 0; u < HB; ++u) {
-            bool ok = rows[u] < g.M && cols[u] < g.N;
+            bool ok = FULL || (rows[u] < g.M && cols[u] < g.N);
             long o = ok ? zc + (long)rows[u] * g.ldaux + cols[u] : zc;
             if (epi & EPI_AUX32) {
               xv[u] = *(const float4*)((const float*)g.aux + o);
@@ -466,25 +468,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
         if (epi & EPI_OUT32) {
 #pragma unroll
           for (int u = 0; u < HB; ++u)
-            if (rows[u] < g.M && cols[u] < g.N) *(float4*)((float*)Cb + zc + (long)rows[u] * g.ldc + cols[u]) = t[u];
+            if (FULL || (rows[u] < g.M && cols[u] < g.N)) *(float4*)((float*)Cb + zc + (long)rows[u] * g.ldc + cols[u]) = t[u];
         } else if (epi & EPI_ACC32) {
           float4 cv[HB];
 #pragma unroll
           for (int u = 0; u < HB; ++u) {
-            bool ok = rows[u] < g.M && cols[u] < g.N;
+            bool ok = FULL || (rows[u] < g.M && cols[u] < g.N);
             long o = ok ? zc + (long)rows[u] * g.ldc + cols[u] : zc;
             cv[u] = *(const float4*)((const float*)Cb + o);
           }
 #pragma unroll
           for (int u = 0; u < HB; ++u)
-            if (rows[u] < g.M && cols[u] < g.N) {
+            if (FULL || (rows[u] < g.M && cols[u] < g.N)) {
               cv[u].x += t[u].x; cv[u].y += t[u].y; cv[u].z += t[u].z; cv[u].w += t[u].w;
               *(float4*)((float*)Cb + zc + (long)rows[u] * g.ldc + cols[u]) = cv[u];
             }
         } else if (epi & EPI_GELU) {
 #pragma unroll
           for (int u = 0; u < HB; ++u)
-            if (rows[u] < g.M && cols[u] < g.N) {
+            if (FULL || (rows[u] < g.M && cols[u] < g.N)) {
               float tv[4] = {t[u].x, t[u].y, t[u].z, t[u].w};
               bf16x4 gv, gp;
 #pragma unroll
@@ -501,7 +503,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
         } else {
 #pragma unroll
           for (int u = 0; u < HB; ++u)
-            if (rows[u] < g.M && cols[u] < g.N) {
+            if (FULL || (rows[u] < g.M && cols[u] < g.N)) {
               bf16x4 ov;
               ov[0] = (bf16)t[u].x; ov[1] = (bf16)t[u].y; ov[2] = (bf16)t[u].z; ov[3] = (bf16)t[u].w;
               *(bf16x4*)((bf16*)Cb + zc + (long)rows[u] * g.ldc + cols[u]) = ov;
@@ -511,10 +513,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
     }
     __builtin_amdgcn_wave_barrier();
   };
-  store_block(std::integral_constant<int, 0>{});
-  if constexpr (MI > 1) store_block(std::integral_constant<int, 1>{});
-  if constexpr (MI > 2) store_block(std::integral_constant<int, 2>{});
-  if constexpr (MI > 3) store_block(std::integral_constant<int, 3>{});
+  auto store_tile = [&](auto FULLC) {
+    store_block(std::integral_constant<int, 0>{}, FULLC);
+    if constexpr (MI > 1) store_block(std::integral_constant<int, 1>{}, FULLC);
+    if constexpr (MI > 2) store_block(std::integral_constant<int, 2>{}, FULLC);
+    if constexpr (MI > 3) store_block(std::integral_constant<int, 3>{}, FULLC);
+  };
+  // interior tiles (nearly all of them) take the path without per-element bounds tests
+  if (m0 + BM <= g.M && n0 + BN <= g.N) store_tile(std::true_type{});
+  else store_tile(std::false_type{});
   static_assert(MI <= 4, "at most four 32-row blocks per wave");
 }
 
