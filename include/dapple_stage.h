@@ -103,8 +103,9 @@ typedef struct {
   uint64_t weight_bytes;    /* bytes of the caller's flat parameter vector */
   uint64_t grad_bytes;      /* fp32 accumulators */
   uint64_t slot_bytes;      /* activations one resident micro-batch keeps from F to B */
-  uint64_t workspace_bytes; /* transient buffers shared by all tasks */
-  uint64_t arena_bytes;     /* grad_bytes + max_slots * slot_bytes + workspace_bytes (+ alignment) */
+  uint64_t workspace_bytes; /* transient buffers shared by all tasks (one copy) */
+  uint64_t arena_bytes;     /* grad_bytes + max_slots * slot_bytes + copies * workspace_bytes (+ alignment);
+                               copies = 2 (one workspace per backward lane), 1 under STAGE_FLAG_RECOMPUTE */
 } stage_sizes;
 
 typedef struct {

@@ -74,6 +74,7 @@ struct Layout {
   // re-computation: a resident micro-batch keeps only its input (and targets); the activations of
   // the task being run live in one of two buffers of act_bytes (0: forward tasks, 1: backward tasks)
   bool recompute = false;
+  int ws_copies = 1;
   size_t act_bytes = 0, st_x = 0, st_aux = 0, ws_act[2] = {0, 0}, ws_ydummy = 0;
   // workspace (bytes)
   // buffers the side stream reads exist twice (layers alternate between the sets)
@@ -200,7 +201,10 @@ void build_layout(const stage_config& c, Layout& L) {
   L.arena_grads = 0;
   L.arena_slots = L.grad_bytes;
   L.arena_ws = L.arena_slots + (size_t)c.max_slots * L.slot_bytes;
-  L.arena_bytes = L.arena_ws + L.workspace_bytes;
+  // two copies of the workspace: consecutive backward tasks of the early-backward order run on
+  // two lanes and must not share temporaries (re-computation keeps one lane and one copy)
+  L.ws_copies = L.recompute ? 1 : 2;
+  L.arena_bytes = L.arena_ws + L.ws_copies * L.workspace_bytes;
 }
 
 struct ProfEvent { hipEvent_t a, b; int cls; double flops; int lane; };
@@ -220,6 +224,8 @@ struct dapple_stage {
   hipStream_t st;         // the caller's stream: the critical path (forward; backward data gradients)
   hipStream_t side = nullptr;  // library-owned: weight / bias / LayerNorm gradient work of a backward task
   hipStream_t fwd = nullptr;   // library-owned: forward tasks inside stage_run_schedule
+  hipStream_t bwd2 = nullptr;  // library-owned: every second backward task inside stage_run_schedule
+  hipEvent_t ev_b2done = nullptr;
   hipStream_t cur = nullptr;   // where the task being enqueued puts its main-line kernels (st or fwd)
   std::vector<hipEvent_t> ev_f, ev_b;  // per slot: forward done (fwd lane), backward done (caller's stream)
   hipEvent_t ev_start = nullptr;
@@ -236,7 +242,8 @@ struct dapple_stage {
   const char* w(size_t elem_off) const { return W + elem_off * E(); }
   float* gr(size_t elem_off) const { return grads + elem_off; }
   char* slot(int s) const { return arena + L.arena_slots + (size_t)s * L.slot_bytes; }
-  char* ws(size_t off) const { return arena + L.arena_ws + off; }
+  size_t ws_shift = 0;  // selects the workspace copy of the task being enqueued
+  char* ws(size_t off) const { return arena + L.arena_ws + ws_shift + off; }
 
   // run one launcher; with profiling on, bracket it with two events
   template <typename Fn>
@@ -246,7 +253,7 @@ struct dapple_stage {
   int fork(int layer, int which) {
     if (dry) return STAGE_OK;
     hipEvent_t e = ev[layer * 5 + which];
-    if (hipEventRecord(e, st) != hipSuccess || hipStreamWaitEvent(side, e, 0) != hipSuccess)
+    if (hipEventRecord(e, cur) != hipSuccess || hipStreamWaitEvent(side, e, 0) != hipSuccess)
       return fail(STAGE_E_DEVICE, "event record / wait failed");
     return STAGE_OK;
   }
@@ -258,7 +265,7 @@ struct dapple_stage {
   }
   int join(int layer) {
     if (dry) return STAGE_OK;
-    if (hipStreamWaitEvent(st, ev[layer * 5 + 4], 0) != hipSuccess) return fail(STAGE_E_DEVICE, "event wait failed");
+    if (hipStreamWaitEvent(cur, ev[layer * 5 + 4], 0) != hipSuccess) return fail(STAGE_E_DEVICE, "event wait failed");
     return STAGE_OK;
   }
 
@@ -274,7 +281,7 @@ struct dapple_stage {
         events.push_back(e);
       }
       pe = &events[events_used++];
-      pe->cls = cls; pe->flops = flops; pe->lane = stream == st ? 0 : (stream == side ? 1 : 2);
+      pe->cls = cls; pe->flops = flops; pe->lane = stream == st ? 0 : (stream == side ? 1 : (stream == fwd ? 2 : 3));
       (void)hipEventRecord(pe->a, stream);
     }
     hipError_t e = fn(stream);
@@ -297,7 +304,7 @@ struct dapple_stage {
           {envi("DAPPLE_TILE_MAIN_BIG"), envi("DAPPLE_TILE_MAIN_MID"), envi("DAPPLE_TILE_MAIN_SMALL")},
           {envi("DAPPLE_TILE_SIDE_BIG"), envi("DAPPLE_TILE_SIDE_MID"), envi("DAPPLE_TILE_SIDE_SMALL")},
           {envi("DAPPLE_TILE_FWD_BIG"), envi("DAPPLE_TILE_FWD_MID"), envi("DAPPLE_TILE_FWD_SMALL")}};
-      const int lane = s_ == st ? 0 : (s_ == side ? 1 : 2);
+      const int lane = (s_ == st || s_ == bwd2) ? 0 : (s_ == side ? 1 : 2);
       const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
       const int cl = t128 > 256 ? 0 : (t128 >= 192 ? 1 : 2);
       if (!g.tile) g.tile = tab[lane][cl];
@@ -690,7 +697,8 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
       delete h;
       return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
     }
-    if (hipStreamCreateWithFlags(&h->fwd, hipStreamNonBlocking) != hipSuccess) {
+    if (hipStreamCreateWithFlags(&h->fwd, hipStreamNonBlocking) != hipSuccess ||
+        hipStreamCreateWithFlags(&h->bwd2, hipStreamNonBlocking) != hipSuccess) {
       delete h;
       return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
     }
@@ -702,6 +710,7 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
     for (auto& e : h->ev_f) all.push_back(&e);
     for (auto& e : h->ev_b) all.push_back(&e);
     all.push_back(&h->ev_start);
+    all.push_back(&h->ev_b2done);
     for (hipEvent_t* e : all)
       if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) {
         delete h;
@@ -725,12 +734,15 @@ int stage_destroy(stage_handle h) {
     (void)hipStreamSynchronize(h->st);
     if (h->side) (void)hipStreamSynchronize(h->side);
     if (h->fwd) (void)hipStreamSynchronize(h->fwd);
+    if (h->bwd2) (void)hipStreamSynchronize(h->bwd2);
   }
   for (auto& e : h->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
   for (auto& e : h->ev) (void)hipEventDestroy(e);
   for (auto& e : h->ev_f) (void)hipEventDestroy(e);
   for (auto& e : h->ev_b) (void)hipEventDestroy(e);
   if (h->ev_start) (void)hipEventDestroy(h->ev_start);
+  if (h->ev_b2done) (void)hipEventDestroy(h->ev_b2done);
+  if (h->bwd2) (void)hipStreamDestroy(h->bwd2);
   if (h->side && h->side != h->st) (void)hipStreamDestroy(h->side);
   if (h->fwd) (void)hipStreamDestroy(h->fwd);
   delete h;
@@ -842,9 +854,20 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
   std::vector<char> b_pending(h->cfg.max_slots, 0);
   int last_f_slot = -1;
   auto hip_ok = [](hipError_t e) { return e == hipSuccess ? STAGE_OK : fail(STAGE_E_DEVICE, "%s", hipGetErrorString(e)); };
+  // Early-backward order, plain stages: consecutive backward tasks alternate between the caller's
+  // stream and a second backward stream (each with its own copy of the workspace), so the head of
+  // B_{j+1} overlaps the tail of B_j.  Their accumulator updates still happen in list order: all of
+  // them are issued, in host order, on the one side stream.  (A first or last stage also
+  // accumulates on its backward stream -- embedding tables, head -- and keeps one backward lane.)
+  static const int bwd_lanes_env = envi("DAPPLE_BWD_LANES");
+  const bool two = lanes && !strict && h->L.ws_copies == 2 && !h->cfg.has_embedding && !h->cfg.has_mlm_head &&
+                   !h->no_side && bwd_lanes_env != 1;
+  int n_bwd = 0;
+  bool used_b2 = false;
   if (lanes) {
     TRY(hip_ok(hipEventRecord(h->ev_start, h->st)));
     TRY(hip_ok(hipStreamWaitEvent(h->fwd, h->ev_start, 0)));
+    if (two) TRY(hip_ok(hipStreamWaitEvent(h->bwd2, h->ev_start, 0)));
   }
   int rc = STAGE_OK;
   for (int32_t op : ops) {
@@ -865,14 +888,23 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
       } else if ((rc = stage_fwd(h, m, xs ? xs[m] : nullptr, ys ? ys[m] : nullptr, auxs ? auxs[m] : nullptr)) != STAGE_OK) break;
     } else {
       int s = -1;
+      const bool second = two && (n_bwd & 1);
+      hipStream_t bs = second ? h->bwd2 : h->st;
+      ++n_bwd;
       if (lanes) {
         s = find_slot(h, m);
         int w = strict ? last_f_slot : s;
-        if (w >= 0 && (rc = hip_ok(hipStreamWaitEvent(h->st, h->ev_f[w], 0))) != STAGE_OK) break;
+        if (w >= 0 && (rc = hip_ok(hipStreamWaitEvent(bs, h->ev_f[w], 0))) != STAGE_OK) break;
       }
-      if ((rc = stage_bwd(h, m, dys ? dys[m] : nullptr, dxs ? dxs[m] : nullptr)) != STAGE_OK) break;
+      h->cur = bs;
+      h->ws_shift = second ? h->L.workspace_bytes : 0;
+      rc = stage_bwd(h, m, dys ? dys[m] : nullptr, dxs ? dxs[m] : nullptr);
+      h->cur = h->st;
+      h->ws_shift = 0;
+      if (rc != STAGE_OK) break;
+      used_b2 = used_b2 || second;
       if (lanes) {
-        if ((rc = hip_ok(hipEventRecord(h->ev_b[s], h->st))) != STAGE_OK) break;
+        if ((rc = hip_ok(hipEventRecord(h->ev_b[s], bs))) != STAGE_OK) break;
         b_pending[s] = 1;
       }
     }
@@ -880,6 +912,11 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
   // the caller's stream ends behind everything the forward lane was given, also on an error
   if (lanes && last_f_slot >= 0) {
     int rc2 = hip_ok(hipStreamWaitEvent(h->st, h->ev_f[last_f_slot], 0));
+    if (rc == STAGE_OK) rc = rc2;
+  }
+  if (used_b2) {  // ... and behind the second backward lane
+    int rc2 = hip_ok(hipEventRecord(h->ev_b2done, h->bwd2));
+    if (rc2 == STAGE_OK) rc2 = hip_ok(hipStreamWaitEvent(h->st, h->ev_b2done, 0));
     if (rc == STAGE_OK) rc = rc2;
   }
   return rc;
@@ -947,7 +984,8 @@ int stage_profile_read(stage_handle h, int n, uint64_t* launches, double* ms, do
   if (!h || !launches || !ms || !flops) return fail(STAGE_E_NULL, "arguments must not be NULL");
   if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
-  if (!h->dry && h->fwd && hipStreamSynchronize(h->fwd) != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed");
+  if (!h->dry && h->fwd && (hipStreamSynchronize(h->fwd) != hipSuccess || hipStreamSynchronize(h->bwd2) != hipSuccess))
+    return fail(STAGE_E_DEVICE, "stream synchronise failed");
   for (int i = 0; i < n; ++i) { launches[i] = 0; ms[i] = 0; flops[i] = 0; }
   if (const char* path = getenv("DAPPLE_TIMELINE")) {
     // debugging aid: every launch of the profiled steps as "class,lane,start_ms,end_ms" (lane 0 = caller's
