@@ -222,7 +222,10 @@ struct dapple_stage {
   char* arena;
   float* grads;
   hipStream_t st;         // the caller's stream: the critical path (forward; backward data gradients)
-  hipStream_t side = nullptr;  // library-owned: weight / bias / LayerNorm gradient work of a backward task
+  // library-owned: weight / bias / LayerNorm gradient work of a backward task.  side2 == side unless
+  // DAPPLE_SIDE_LANES=2; then each gradient tensor is always on the same one of the two (side: W2, b2,
+  // ln2, W1, b1; side2: ln1, bo, Wq..Wo, bq..bv), so the updates of any one tensor stay in task order
+  hipStream_t side = nullptr, side2 = nullptr;
   hipStream_t fwd = nullptr;   // library-owned: forward tasks inside stage_run_schedule
   hipStream_t bwd2 = nullptr;  // library-owned: every second backward task inside stage_run_schedule
   hipEvent_t ev_b2done = nullptr;
@@ -230,7 +233,7 @@ struct dapple_stage {
   std::vector<hipEvent_t> ev_f, ev_b;  // per slot: forward done (fwd lane), backward done (caller's stream)
   hipEvent_t ev_start = nullptr;
   bool serial = false, no_side = false;
-  std::vector<hipEvent_t> ev;  // per layer: 4 "inputs ready" events (main -> side) + 1 "layer done" (side -> main)
+  std::vector<hipEvent_t> ev;  // per layer: 4 "inputs ready" events (main -> side) + 2 "layer done" (each side stream -> main)
   std::vector<int> slot_of_mb;   // slot -> micro-batch id, -1 = free
   int live = 0, peak_live = 0;
   uint64_t fwd_tasks = 0, bwd_tasks = 0, launches = 0;
@@ -252,20 +255,22 @@ struct dapple_stage {
   // main -> side: the side stream may start once the main stream has passed this point
   int fork(int layer, int which) {
     if (dry) return STAGE_OK;
-    hipEvent_t e = ev[layer * 5 + which];
-    if (hipEventRecord(e, cur) != hipSuccess || hipStreamWaitEvent(side, e, 0) != hipSuccess)
+    hipEvent_t e = ev[layer * 6 + which];
+    if (hipEventRecord(e, cur) != hipSuccess || hipStreamWaitEvent(which < 2 ? side : side2, e, 0) != hipSuccess)
       return fail(STAGE_E_DEVICE, "event record / wait failed");
     return STAGE_OK;
   }
   // side -> main, in two halves: mark the side work of a layer done; later make main wait for it
   int side_done(int layer) {
     if (dry) return STAGE_OK;
-    if (hipEventRecord(ev[layer * 5 + 4], side) != hipSuccess) return fail(STAGE_E_DEVICE, "event record failed");
+    if (hipEventRecord(ev[layer * 6 + 4], side) != hipSuccess || hipEventRecord(ev[layer * 6 + 5], side2) != hipSuccess)
+      return fail(STAGE_E_DEVICE, "event record failed");
     return STAGE_OK;
   }
   int join(int layer) {
     if (dry) return STAGE_OK;
-    if (hipStreamWaitEvent(cur, ev[layer * 5 + 4], 0) != hipSuccess) return fail(STAGE_E_DEVICE, "event wait failed");
+    if (hipStreamWaitEvent(cur, ev[layer * 6 + 4], 0) != hipSuccess || hipStreamWaitEvent(cur, ev[layer * 6 + 5], 0) != hipSuccess)
+      return fail(STAGE_E_DEVICE, "event wait failed");
     return STAGE_OK;
   }
 
@@ -281,7 +286,7 @@ struct dapple_stage {
         events.push_back(e);
       }
       pe = &events[events_used++];
-      pe->cls = cls; pe->flops = flops; pe->lane = stream == st ? 0 : (stream == side ? 1 : (stream == fwd ? 2 : 3));
+      pe->cls = cls; pe->flops = flops; pe->lane = stream == st ? 0 : (stream == side ? 1 : (stream == fwd ? 2 : (stream == bwd2 ? 3 : 4)));
       (void)hipEventRecord(pe->a, stream);
     }
     hipError_t e = fn(stream);
@@ -291,20 +296,20 @@ struct dapple_stage {
     return STAGE_OK;
   }
 
-  int gemm(int cls, GemmArgs g, hipStream_t stream = nullptr, bool on_side = false) {
+  int gemm(int cls, GemmArgs g, hipStream_t stream = nullptr, bool on_side = false, bool second_side = false) {
     if (g.kseg_len == 0) g.kseg_len = g.K;
     if (g.k_valid == 0) g.k_valid = g.K;
     if (g.m_valid == 0) g.m_valid = g.M;
     if (g.n_valid == 0) g.n_valid = g.N;
     if (g.batch == 0) g.batch = 1;
     double flops = 2.0 * g.M * g.N * (double)g.K * g.batch;
-    hipStream_t s_ = on_side ? side : cur;
+    hipStream_t s_ = on_side ? (second_side ? side2 : side) : cur;
     {  // tuning: DAPPLE_TILE_<lane>_<BIG|MID|SMALL> picks the tile configuration per lane and size class
       static const int tab[3][3] = {
           {envi("DAPPLE_TILE_MAIN_BIG"), envi("DAPPLE_TILE_MAIN_MID"), envi("DAPPLE_TILE_MAIN_SMALL")},
           {envi("DAPPLE_TILE_SIDE_BIG"), envi("DAPPLE_TILE_SIDE_MID"), envi("DAPPLE_TILE_SIDE_SMALL")},
           {envi("DAPPLE_TILE_FWD_BIG"), envi("DAPPLE_TILE_FWD_MID"), envi("DAPPLE_TILE_FWD_SMALL")}};
-      const int lane = (s_ == st || s_ == bwd2) ? 0 : (s_ == side ? 1 : 2);
+      const int lane = (s_ == st || s_ == bwd2) ? 0 : ((s_ == side || s_ == side2) ? 1 : 2);
       const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
       const int cl = t128 > 256 ? 0 : (t128 >= 192 ? 1 : 2);
       if (!g.tile) g.tile = tab[lane][cl];
@@ -532,7 +537,7 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     }
     TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dy1, z1, dt == DT_BF16, st1, w(p.ln1g), dz1, part_ln1, &nblk, T, H, q); }));
     TRY(fork(l, 2));
-    TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln1, nblk, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), q); }));
+    TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln1, nblk, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), q); }));
     {  // dctx = dz1 Wo^T
       GemmArgs ga{};
       ga.A = dz1; ga.lda = H; ga.B = w(p.Wo); ga.ldb = H; ga.C = dctx; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H;
@@ -548,7 +553,7 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       TRY(run(KC_ATTN_BWD, fl, [&](hipStream_t q) { return launch_attn_bwd(dt, aa, q); }));
     }
     TRY(fork(l, 3));
-    TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) {
+    TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) {
       return launch_colsum(dt, dqkv, T, H, H, part_qkv, gr(p.bq), 3, (long)T * H, (long)pstride, q);
     }));
     {  // dWq, dWk, dWv += x^T dq, x^T dk, x^T dv and dWo += ctx^T dz1: four products of one
@@ -561,7 +566,7 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       }
       ga.Az[3] = ctx; ga.Bz[3] = dz1; ga.Cz[3] = gr(p.Wo);
       ga.A = ga.Az[0]; ga.B = ga.Bz[0]; ga.C = ga.Cz[0];
-      TRY(gemm(KC_GEMM_WGRAD, ga, nullptr, true));
+      TRY(gemm(KC_GEMM_WGRAD, ga, nullptr, true, true));
     }
     TRY(side_done(l));
     {  // dx = dq Wq^T + dk Wk^T + dv Wv^T + dz1 (residual branch): one product over K = 3H
@@ -692,17 +697,27 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
       h->no_side = v == 1 || v == 3;
     }
     if (h->no_side) {
-      h->side = h->st;
-    } else if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) {
-      delete h;
-      return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
+      h->side = h->side2 = h->st;
+    } else {
+      if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) {
+        delete h;
+        return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
+      }
+      // one side stream by default: a second one (DAPPLE_SIDE_LANES=2) takes more from the backward
+      // lanes than it gives (measured 1957 against 2108 samples/s on the BERT-Large-shaped stage)
+      if (envi("DAPPLE_SIDE_LANES") != 2) {
+        h->side2 = h->side;
+      } else if (hipStreamCreateWithFlags(&h->side2, hipStreamNonBlocking) != hipSuccess) {
+        delete h;
+        return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
+      }
     }
     if (hipStreamCreateWithFlags(&h->fwd, hipStreamNonBlocking) != hipSuccess ||
         hipStreamCreateWithFlags(&h->bwd2, hipStreamNonBlocking) != hipSuccess) {
       delete h;
       return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
     }
-    h->ev.resize((size_t)cfg->n_layers * 5);
+    h->ev.resize((size_t)cfg->n_layers * 6);
     h->ev_f.resize(cfg->max_slots);
     h->ev_b.resize(cfg->max_slots);
     std::vector<hipEvent_t*> all;
@@ -733,6 +748,7 @@ int stage_destroy(stage_handle h) {
   if (!h->dry) {
     (void)hipStreamSynchronize(h->st);
     if (h->side) (void)hipStreamSynchronize(h->side);
+    if (h->side2) (void)hipStreamSynchronize(h->side2);
     if (h->fwd) (void)hipStreamSynchronize(h->fwd);
     if (h->bwd2) (void)hipStreamSynchronize(h->bwd2);
   }
@@ -743,6 +759,7 @@ int stage_destroy(stage_handle h) {
   if (h->ev_start) (void)hipEventDestroy(h->ev_start);
   if (h->ev_b2done) (void)hipEventDestroy(h->ev_b2done);
   if (h->bwd2) (void)hipStreamDestroy(h->bwd2);
+  if (h->side2 && h->side2 != h->side && h->side2 != h->st) (void)hipStreamDestroy(h->side2);
   if (h->side && h->side != h->st) (void)hipStreamDestroy(h->side);
   if (h->fwd) (void)hipStreamDestroy(h->fwd);
   delete h;
@@ -973,7 +990,8 @@ int stage_reset_stats(stage_handle h) {
 
 int stage_profile_enable(stage_handle h, int on) {
   if (!h) return fail(STAGE_E_NULL, "handle is NULL");
-  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess))
+  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess ||
+                  hipStreamSynchronize(h->side2) != hipSuccess))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
   h->profiling = on != 0;
   h->events_used = 0;
@@ -982,7 +1000,8 @@ int stage_profile_enable(stage_handle h, int on) {
 
 int stage_profile_read(stage_handle h, int n, uint64_t* launches, double* ms, double* flops) {
   if (!h || !launches || !ms || !flops) return fail(STAGE_E_NULL, "arguments must not be NULL");
-  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess))
+  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess ||
+                  hipStreamSynchronize(h->side2) != hipSuccess))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
   if (!h->dry && h->fwd && (hipStreamSynchronize(h->fwd) != hipSuccess || hipStreamSynchronize(h->bwd2) != hipSuccess))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
@@ -1019,6 +1038,7 @@ int stage_sync(stage_handle h) {
   if (h->dry) return STAGE_OK;
   hipError_t e = hipStreamSynchronize(h->st);
   if (e == hipSuccess) e = hipStreamSynchronize(h->side);
+  if (e == hipSuccess) e = hipStreamSynchronize(h->side2);
   if (e != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed: %s", hipGetErrorString(e));
   if (h->cfg.has_mlm_head) {
     int32_t info[2] = {0, 0};
