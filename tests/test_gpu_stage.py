@@ -7,7 +7,7 @@ import pytest
 from oracle import stage_oracle as O
 from paper_2007_01045_amd import binding as B
 from paper_2007_01045_amd import inputs as I
-from tests.stage_util import compare, make_inputs, run_gpu, run_oracle
+from tests.stage_util import c_config, compare, make_inputs, run_gpu, run_oracle, to_np
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -195,3 +195,72 @@ def test_recompute_fp32_first_and_last_stage():
     _recompute_case(emb, 3, 2, B.ORDER_EARLY_BACKWARD)
     head = I.StageConfig(2, 128, 2, 256, 64, 2, 3, 2, "bf16", has_mlm_head=True, vocab=520)
     _recompute_case(head, 3, 2, B.ORDER_EARLY_BACKWARD)
+
+
+# ---- two stages chained on one GPU: y of stage 0 is x of stage 1, dx of stage 1 is dy of stage 0
+def _chained(cfg6, M, dtype_tol):
+    """Split a 6-layer stage in two 3-layer stages, run both in their own early-backward orders
+    (K_0 = 2, K_1 = 1: policy A of section V-C for two stages) with a task interleaving that
+    respects the pipeline's data dependences, through stage_fwd / stage_bwd."""
+    import torch
+    half = I.StageConfig(cfg6.n_layers // 2, cfg6.hidden, cfg6.n_heads, cfg6.ffn, cfg6.seq, cfg6.micro_batch,
+                         M, 2, cfg6.dtype, ln_eps=cfg6.ln_eps)
+    theta, mbs = make_inputs(cfg6, SEED, M)
+    nh = I.n_params(half)
+    assert 2 * nh == theta.size
+    T, H = cfg6.tokens, cfg6.hidden
+    r0, r1 = B.StageRunner(c_config(half, 2), theta[:nh]), B.StageRunner(c_config(half, 1), theta[nh:])
+    try:
+        xs = [r0.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+        dys = [r1.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
+        mid = [r0.empty_act() for _ in range(M)]       # the message forward: y of stage 0
+        ys = [r1.empty_act() for _ in range(M)]
+        dmid = [r1.empty_act() for _ in range(M)]      # the message backward: dx of stage 1
+        dxs = [r0.empty_act() for _ in range(M)]
+        lists = [B.stage_schedule_ops(M, 2, B.ORDER_EARLY_BACKWARD), B.stage_schedule_ops(M, 1, B.ORDER_EARLY_BACKWARD)]
+        pos, done = [0, 0], set()
+        while pos[0] < 2 * M or pos[1] < 2 * M:
+            progressed = False
+            for s in (1, 0):                           # the last stage first: it unblocks backwards
+                if pos[s] == 2 * M:
+                    continue
+                kind, m = lists[s][pos[s]]
+                need = ("F", 0, m) if (s == 1 and kind == "F") else (("B", 1, m) if (s == 0 and kind == "B") else None)
+                if need is not None and need not in done:
+                    continue
+                if s == 0 and kind == "F":
+                    B.stage_fwd(r0.h, m, xs[m].data_ptr(), mid[m].data_ptr())
+                elif s == 1 and kind == "F":
+                    B.stage_fwd(r1.h, m, mid[m].data_ptr(), ys[m].data_ptr())
+                elif s == 1:
+                    B.stage_bwd(r1.h, m, dys[m].data_ptr(), dmid[m].data_ptr())
+                else:
+                    B.stage_bwd(r0.h, m, dmid[m].data_ptr(), dxs[m].data_ptr())
+                done.add((kind, s, m))
+                pos[s] += 1
+                progressed = True
+            assert progressed, "the two task lists deadlock"
+        B.stage_sync(r0.h); B.stage_sync(r1.h)
+        torch.cuda.synchronize()
+        assert B.stage_stats(r0.h).peak_live_slots == min(2, M) and B.stage_stats(r1.h).peak_live_slots == 1
+        got = dict(ys=[to_np(y) for y in ys], dxs=[to_np(d) for d in dxs],
+                   grads=np.concatenate([r0.grads.cpu().numpy(), r1.grads.cpu().numpy()]))
+    finally:
+        r0.close(); r1.close()
+    st, ref = run_oracle(cfg6, theta, mbs, M, 2)
+    compare(cfg6, st, ref, got, dtype_tol, M)
+    return theta, mbs, got
+
+
+def test_two_chained_stages_fp32_equal_the_single_stage_bitwise():
+    cfg6 = I.StageConfig(6, 64, 4, 128, 16, 2, 3, 2, "f32", ln_eps=1e-5)
+    theta, mbs, got = _chained(cfg6, 3, TOL_F32)
+    one = run_gpu(cfg6, theta, mbs, 3, 2, B.ORDER_EARLY_BACKWARD)
+    assert np.array_equal(one["grads"], got["grads"])
+    for m in range(3):
+        assert np.array_equal(one["ys"][m], got["ys"][m]) and np.array_equal(one["dxs"][m], got["dxs"][m])
+
+
+def test_two_chained_stages_bf16_follow_the_oracle():
+    # the boundary tensor is bf16 here, inside one stage the residual stream stays fp32: not bitwise
+    _chained(I.StageConfig(6, 256, 4, 512, 128, 2, 3, 2, "bf16"), 3, TOL_BF16)
