@@ -36,7 +36,12 @@ def stage_flops(cfg, M):
     (QK^T and PV); the backward is twice that."""
     T, H, F, s = cfg.tokens, cfg.hidden, cfg.ffn, cfg.seq
     fwd = 8.0 * T * H * H + 4.0 * T * H * F + 4.0 * T * s * H
-    return 3.0 * fwd * cfg.n_layers * M
+    head = 0.0
+    if cfg.has_mlm_head:  # transform and vocabulary projection on the ceil(0.15 T) predicted rows
+        import math
+        n = math.ceil(0.15 * T)
+        head = 2.0 * n * H * H + 2.0 * n * H * cfg.vocab
+    return 3.0 * (fwd * cfg.n_layers + head) * M
 
 
 def cpu_baseline(cfg, seed, M_sample, K_sample):
@@ -49,12 +54,14 @@ def cpu_baseline(cfg, seed, M_sample, K_sample):
     except Exception:
         cores = os.cpu_count() or 1
     theta = I.make_params(cfg, seed).astype(np.float64)
-    st = O.Stage(I.param_layout(cfg), theta, cfg.n_layers, cfg.n_heads, cfg.ln_eps)
+    st = O.Stage(I.param_layout(cfg), theta, cfg.n_layers, cfg.n_heads, cfg.ln_eps, cfg.has_embedding,
+                 cfg.has_mlm_head, 1.0)
     mbs = [I.make_microbatch(cfg, seed, m) for m in range(M_sample)]
-    xs = [mb["x"].astype(np.float64) for mb in mbs]
-    dys = [mb["dy"].astype(np.float64) for mb in mbs]
+    xs = [mb["ids"] if cfg.has_embedding else mb["x"].astype(np.float64) for mb in mbs]
+    dys = None if cfg.has_mlm_head else [mb["dy"].astype(np.float64) for mb in mbs]
+    tg = [mb["targets"] for mb in mbs] if cfg.has_mlm_head else None
     t0 = time.perf_counter()
-    O.run_schedule(st, M_sample, K_sample, O.EARLY_BACKWARD, xs, dys)
+    O.run_schedule(st, M_sample, K_sample, O.EARLY_BACKWARD, xs, dys, tg)
     dt = time.perf_counter() - t0
     return {"value": M_sample * cfg.micro_batch / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
             "sample": f"{M_sample} of the {cfg.M} micro-batches (K={K_sample}) of the same stage, float64 numpy, "
@@ -101,16 +108,18 @@ def main():
                                             ("early_backward_recompute", B.ORDER_EARLY_BACKWARD, K, B.FLAG_RECOMPUTE),
                                             ("early_backward", B.ORDER_EARLY_BACKWARD, K, 0)):
         r = B.StageRunner(c_config(cfg, slots, flags=flags), theta)
-        xs = [r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
-        dys = [r.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
-        ys = [r.empty_act() for _ in range(M)]
-        dxs = [r.empty_act() for _ in range(M)]
-        ptr = lambda ts: [t.data_ptr() for t in ts]
-        px, pdy, py, pdx = ptr(xs), ptr(dys), ptr(ys), ptr(dxs)
+        emb, head = cfg.has_embedding, cfg.has_mlm_head
+        xs = [r.to_dev(mb["ids"].reshape(T).astype(np.int32)) if emb else r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+        dys = None if head else [r.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
+        auxs = [r.to_dev(mb["targets"].reshape(T).astype(np.int32)) for mb in mbs] if head else None
+        ys = [torch.zeros(1, dtype=torch.float32, device="cuda") if head else r.empty_act() for _ in range(M)]
+        dxs = None if emb else [r.empty_act() for _ in range(M)]
+        ptr = lambda ts: None if ts is None else [t.data_ptr() for t in ts]
+        px, pdy, py, pdx, paux = ptr(xs), ptr(dys), ptr(ys), ptr(dxs), ptr(auxs)
 
         def step():
             B.stage_zero_grads(r.h)
-            B.stage_run_schedule(r.h, M, K, order, px, pdy, py, pdx)
+            B.stage_run_schedule(r.h, M, K, order, px, pdy, py, pdx, paux)
 
         for _ in range(args.warmup):
             step()
@@ -128,7 +137,7 @@ def main():
         if order_name == "early_backward":
             runner = (r, step)
         else:
-            del xs, dys, ys, dxs
+            del xs, dys, ys, dxs, auxs
             r.close()
             del r
             torch.cuda.empty_cache()
