@@ -97,6 +97,22 @@ hipError_t launch_partial_reduce(const float* partial, int nblk, int nvec, int H
 // element strides zs_x (X) and zs_out (out); partial needs nb * ceil(rows/64) * cols floats
 hipError_t launch_colsum(Dtype dt, const void* X, int rows, int cols, int ld, float* partial,
                          float* out, int nb, long zs_x, long zs_out, hipStream_t st);
+// first stage of launch_colsum alone: partial[(z*nblk + blk)*PS + c], blk < *nblk = ceil(rows/64) blocks of 64 rows
+hipError_t launch_colsum_partials(Dtype dt, const void* X, int rows, int cols, int ld, float* partial, int nb, long zs_x,
+                                  int* nblk, int* PS_out, hipStream_t st);
+// out[c] += sum over blk (ascending, in the order of launch_partial_reduce) of partial[blk*stride + c], c < cols,
+// for up to 12 such jobs in one launch
+struct ReduceJob {
+  const float* partial;
+  float* out;
+  int nblk, cols;
+  long stride;
+};
+struct ReduceJobs {
+  ReduceJob j[12];
+  int n;
+};
+hipError_t launch_reduce_jobs(const ReduceJobs& J, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_zero(void* dst, size_t bytes, hipStream_t st);
 

@@ -257,6 +257,39 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const float* __rest
   }
 }
 
+// Several partial_reduce jobs in one launch (blockIdx.y = job): the summation of a job is that of
+// partial_reduce_kernel, addition for addition.
+__global__ __launch_bounds__(256) void reduce_jobs_kernel(ReduceJobs J) {
+  __shared__ float red[4][64];
+  const ReduceJob& job = J.j[blockIdx.y];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  if (blockIdx.x * 64 >= job.cols) return;   // the whole workgroup: no barrier is skipped by part of it
+  float t = 0.f;
+  if (c < job.cols) {
+    const float* p = job.partial + c;
+    const long stride = job.stride;
+    const int nblk = job.nblk;
+    int b = w;
+    for (; b + 28 < nblk; b += 32) {
+      float x[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) x[u] = p[(long)(b + 4 * u) * stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t += x[u];
+    }
+    for (; b < nblk; b += 4) t += p[(long)b * stride];
+  }
+  red[w][lane] = t;
+  __syncthreads();
+  if (w == 0 && c < job.cols) {
+    float r = red[0][lane] + red[1][lane];
+    r += red[2][lane];
+    r += red[3][lane];
+    job.out[c] += r;
+  }
+}
+
 // ------------------------------------------------------------------ column sums
 constexpr int CS_ROWS = 64;
 template <typename T>
@@ -404,6 +437,32 @@ hipError_t launch_colsum(Dtype dt, const void* X, int rows, int cols, int ld, fl
   dim3 grid((cols + 63) / 64, 1, nb);
   hipLaunchKernelGGL(partial_reduce_kernel, grid, dim3(256), 0, st, partial, nrb, 1, cols, out, nullptr, nullptr,
                      (long)nrb * PS, zs_out, PS);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum_partials(Dtype dt, const void* X, int rows, int cols, int ld, float* partial, int nb, long zs_x,
+                                  int* nblk, int* PS_out, hipStream_t st) {
+  int nrb = (rows + CS_ROWS - 1) / CS_ROWS;
+  int vec = dt == DT_BF16 ? 8 : 4;
+  int PS = (cols + vec - 1) / vec * vec;
+  *nblk = nrb;
+  *PS_out = PS;
+  if (dt == DT_BF16) {
+    dim3 grid((cols + 64 * 8 - 1) / (64 * 8), nrb, nb);
+    hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, rows, cols, ld, partial, zs_x, PS);
+  } else {
+    dim3 grid((cols + 64 * 4 - 1) / (64 * 4), nrb, nb);
+    hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, rows, cols, ld, partial, zs_x, PS);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_jobs(const ReduceJobs& J, hipStream_t st) {
+  if (J.n <= 0) return hipSuccess;
+  int maxc = 0;
+  for (int i = 0; i < J.n; ++i) maxc = J.j[i].cols > maxc ? J.j[i].cols : maxc;
+  dim3 grid((maxc + 63) / 64, J.n);
+  hipLaunchKernelGGL(reduce_jobs_kernel, grid, dim3(256), 0, st, J);
   return hipGetLastError();
 }
 

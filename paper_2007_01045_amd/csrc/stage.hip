@@ -313,6 +313,8 @@ struct dapple_stage {
       const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
       const int cl = t128 > 256 ? 0 : (t128 >= 192 ? 1 : 2);
       if (!g.tile) g.tile = tab[lane][cl];
+      static const int deep[3] = {envi("DAPPLE_TILE_MAIN_DEEP"), envi("DAPPLE_TILE_SIDE_DEEP"), envi("DAPPLE_TILE_FWD_DEEP")};
+      if (cl == 2 && g.K >= 2048 && deep[lane]) g.tile = deep[lane];  // few tiles, long K
     }
     return run_on(s_, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); });
   }
@@ -508,7 +510,14 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     // y = LN(z2): dz2, and block partial sums for the gradients of ln2 gain/shift and of b2
     TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dyin, z2, dt == DT_BF16, st2, w(p.ln2g), dz2, part_ln2, &nblk, T, H, q); }));
     TRY(fork(l, 0));
-    TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln2, nblk, 3, H, gr(p.ln2g), gr(p.ln2b), gr(p.b2), q); }));
+    // One side stream: the layer's bias and LayerNorm-parameter reductions wait and go out as ONE
+    // launch after the last weight-gradient product (the side stream is the longest chain of a
+    // step, and a small kernel costs it a dispatch of ~15 us when the GPU is full).  Each
+    // reduction adds in the same order as the stand-alone kernels.
+    const bool merged = side2 == side;
+    const int nblk_ln2 = nblk;
+    if (!merged)
+      TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln2, nblk, 3, H, gr(p.ln2g), gr(p.ln2b), gr(p.b2), q); }));
     {  // dW2 += g^T dz2
       GemmArgs ga{};
       ga.A = g; ga.lda = F; ga.a_kstrided = 1; ga.B = dz2; ga.ldb = H; ga.b_kstrided = 1;
@@ -522,7 +531,11 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
     TRY(fork(l, 1));
-    TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_colsum(dt, du, T, F, F, part_du, gr(p.b1), 1, 0, 0, q); }));
+    int nblk_du = 0, ps_du = 0;
+    if (merged)
+      TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_colsum_partials(dt, du, T, F, F, part_du, 1, 0, &nblk_du, &ps_du, q); }));
+    else
+      TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_colsum(dt, du, T, F, F, part_du, gr(p.b1), 1, 0, 0, q); }));
     {  // dW1 += y1^T du
       GemmArgs ga{};
       ga.A = y1; ga.lda = H; ga.a_kstrided = 1; ga.B = du; ga.ldb = F; ga.b_kstrided = 1;
@@ -537,7 +550,9 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     }
     TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dy1, z1, dt == DT_BF16, st1, w(p.ln1g), dz1, part_ln1, &nblk, T, H, q); }));
     TRY(fork(l, 2));
-    TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln1, nblk, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), q); }));
+    const int nblk_ln1 = nblk;
+    if (!merged)
+      TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln1, nblk, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), q); }));
     {  // dctx = dz1 Wo^T
       GemmArgs ga{};
       ga.A = dz1; ga.lda = H; ga.B = w(p.Wo); ga.ldb = H; ga.C = dctx; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H;
@@ -553,9 +568,15 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       TRY(run(KC_ATTN_BWD, fl, [&](hipStream_t q) { return launch_attn_bwd(dt, aa, q); }));
     }
     TRY(fork(l, 3));
-    TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) {
-      return launch_colsum(dt, dqkv, T, H, H, part_qkv, gr(p.bq), 3, (long)T * H, (long)pstride, q);
-    }));
+    int nblk_q = 0, ps_q = 0;
+    if (merged)
+      TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) {
+        return launch_colsum_partials(dt, dqkv, T, H, H, part_qkv, 3, (long)T * H, &nblk_q, &ps_q, q);
+      }));
+    else
+      TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) {
+        return launch_colsum(dt, dqkv, T, H, H, part_qkv, gr(p.bq), 3, (long)T * H, (long)pstride, q);
+      }));
     {  // dWq, dWk, dWv += x^T dq, x^T dk, x^T dv and dWo += ctx^T dz1: four products of one
        // shape in one launch (alone, each would leave most of the CUs idle)
       GemmArgs ga{};
@@ -567,6 +588,19 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       ga.Az[3] = ctx; ga.Bz[3] = dz1; ga.Cz[3] = gr(p.Wo);
       ga.A = ga.Az[0]; ga.B = ga.Bz[0]; ga.C = ga.Cz[0];
       TRY(gemm(KC_GEMM_WGRAD, ga, nullptr, true, true));
+    }
+    if (merged) {
+      ReduceJobs J{};
+      auto add = [&](const float* partial, long stride, int nb, int cols, float* out) {
+        J.j[J.n++] = ReduceJob{partial, out, nb, cols, stride};
+      };
+      float* o2[3] = {gr(p.ln2g), gr(p.ln2b), gr(p.b2)};
+      float* o1[3] = {gr(p.ln1g), gr(p.ln1b), gr(p.bo)};
+      for (int v = 0; v < 3; ++v) add(part_ln2 + (size_t)v * H, 3L * H, nblk_ln2, H, o2[v]);
+      add(part_du, ps_du, nblk_du, F, gr(p.b1));
+      for (int v = 0; v < 3; ++v) add(part_ln1 + (size_t)v * H, 3L * H, nblk_ln1, H, o1[v]);
+      for (int z = 0; z < 3; ++z) add(part_qkv + (size_t)z * nblk_q * ps_q, ps_q, nblk_q, H, gr(p.bq) + (size_t)z * pstride);
+      TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_reduce_jobs(J, q); }));
     }
     TRY(side_done(l));
     {  // dx = dq Wq^T + dk Wk^T + dv Wv^T + dz1 (residual branch): one product over K = 3H
