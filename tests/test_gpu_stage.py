@@ -264,3 +264,18 @@ def test_two_chained_stages_fp32_equal_the_single_stage_bitwise():
 def test_two_chained_stages_bf16_follow_the_oracle():
     # the boundary tensor is bf16 here, inside one stage the residual stream stays fp32: not bitwise
     _chained(I.StageConfig(6, 256, 4, 512, 128, 2, 3, 2, "bf16"), 3, TOL_BF16)
+
+
+@pytest.mark.parametrize("M,K", [(1, 1), (2, 1), (3, 2), (5, 3), (7, 2), (4, 4), (6, 8)])
+def test_lanes_do_not_change_a_bit_for_any_depth(M, K):
+    # forward lane, two backward lanes and the side lane against the strictly serial GPipe order
+    cfg = I.StageConfig(2, 128, 2, 256, 64, 2, M, K, "bf16")
+    theta, mbs = make_inputs(cfg, SEED, M)
+    a = run_gpu(cfg, theta, mbs, M, K, B.ORDER_EARLY_BACKWARD)
+    b = run_gpu(cfg, theta, mbs, M, K, B.ORDER_GPIPE)
+    c = run_gpu(cfg, theta, mbs, M, K, B.ORDER_EARLY_BACKWARD, flags=B.FLAG_RECOMPUTE)
+    assert np.array_equal(a["grads"], b["grads"]) and np.array_equal(a["grads"], c["grads"])
+    for m in range(M):
+        assert np.array_equal(a["ys"][m], b["ys"][m]) and np.array_equal(a["dxs"][m], b["dxs"][m])
+        assert np.array_equal(a["dxs"][m], c["dxs"][m])
+    assert a["stats"]["peak_live"] == min(K, M) and b["stats"]["peak_live"] == M
