@@ -181,6 +181,10 @@ __device__ __forceinline__ bf16x8 acc_to_operand(const float (&p)[16], int ks) {
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
+// 2^x for x <= 0 as the bare v_exp_f32: the library exp2f wraps it in three more instructions that
+// rescale denormal results, and a probability below 2^-126 may as well be zero
+__device__ __forceinline__ float exp2_neg(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ f32x16 zero16() {
   f32x16 z;
 #pragma unroll
@@ -249,22 +253,26 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnArgs a, float scale2) {
     __builtin_amdgcn_sched_barrier(0);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     float mn = fmaxf(m, mx);
-    float alpha = exp2f(m - mn);
+    float alpha = exp2_neg(m - mn);
     float rs = 0.f;
 #pragma unroll
     for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        p[kb2][v] = exp2f(p[kb2][v] - mn);
+        p[kb2][v] = exp2_neg(p[kb2][v] - mn);
         rs += p[kb2][v];
       }
     rs += __shfl_xor(rs, 32, 64);
     l = l * alpha + rs;
     m = mn;
+    // the running maximum of most rows settles after the first key blocks: skip the rescale of
+    // the 32 accumulator registers when no lane of the wave needs it (alpha == 1 exactly)
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+        for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+    }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       bf16x8 pf = acc_to_operand(p[ks >> 1], ks & 1);
@@ -370,7 +378,7 @@ __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, 
         float Lv[4] = {L4.x, L4.y, L4.z, L4.w}, Dv[4] = {D4.x, D4.y, D4.z, D4.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          float pv = exp2f(sa[4 * blk + e] * scale2 - Lv[e]);
+          float pv = exp2_neg(sa[4 * blk + e] * scale2 - Lv[e]);
           p[4 * blk + e] = pv;
           ds[4 * blk + e] = pv * (dp[4 * blk + e] - Dv[e]);
         }
@@ -483,7 +491,7 @@ __global__ __launch_bounds__(256) void attn_dq_mfma(AttnArgs a, float scale2, fl
       __builtin_amdgcn_sched_barrier(0);
       float ds[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) ds[v] = exp2f(sa[v] * scale2 - Lq) * (dp[v] - Dq);
+      for (int v = 0; v < 16; ++v) ds[v] = exp2_neg(sa[v] * scale2 - Lq) * (dp[v] - Dq);
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
         bf16x8 dsf = acc_to_operand(ds, ks);
