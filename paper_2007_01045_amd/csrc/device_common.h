@@ -27,7 +27,8 @@ template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf
 __device__ __forceinline__ void gelu_both(float u, float& g, float& gp) {
   float x = fabsf(u) * 0.70710678118654752f;
   float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-  float e = __expf(-x * x);  // = exp(-u^2 / 2)
+  // = exp(-u^2 / 2), as the bare v_exp_f32 (the argument is never positive; a result below 2^-126 may be zero)
+  float e = __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);
   float poly = t * fmaf(t, fmaf(t, fmaf(t, fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f), -0.284496736f),
                         0.254829592f);
   float half_erfc = 0.5f * poly * e;                 // Phi(-|u|)
