@@ -122,10 +122,18 @@ struct OperandTile {
   // row (4 rows cover 256 B); rows of 128 B alternate halves every second row
   static __device__ __forceinline__ int kswz(int k) { return R >= 128 ? (k & 3) << 2 : ((k >> 1) & 1) << 2; }
 
+  // A wave loads NI consecutive 1 KiB chunks of the tile.  The instruction's immediate offset is
+  // added to the global AND to the LDS address, so the loads of a group of up to four chunks share
+  // one M0 (the LDS base) and differ in the immediate; the lane offsets are compensated
+  // (voff_j - 1024 j) and, to stay non-negative, shifted by BIAS, which the kernel takes out of
+  // the buffer's base and adds to its record count.
+  static constexpr int BIAS = 3072;
+  static constexpr int GROUP = NI < 4 ? NI : 4;
+  static_assert(NI % GROUP == 0 && (GROUP == 2 || GROUP == 4), "a wave loads 2, 4 or 8 chunks per operand");
   __device__ __forceinline__ void init(int ld, int r0, int wave, int lane) {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      int pos = (j * NW + wave) * 64 + lane;
+      int pos = (wave * NI + j) * 64 + lane;
       if (!KS) {
         int row = pos >> 3, kc = (pos & 7) ^ ((row >> 1) & 7);
         voff[j] = ((r0 + row) * ld + kc * 8) * 2;
@@ -133,15 +141,16 @@ struct OperandTile {
         int krow = pos / (R / 8), c = (pos % (R / 8)) ^ kswz(krow);
         voff[j] = (krow * ld + r0 + c * 8) * 2;
       }
+      voff[j] += BIAS - (j % GROUP) * 1024;
     }
   }
-  // Request one k-step's slab.  rs: buffer resource whose base is the slab's first element
-  // and whose num_records is the number of valid bytes from there (0 = nothing to read);
-  // LDS_OFF: byte offset of the tile in LDS (ring slot and operand; a constant);
-  // wave_off = wave * 1024.  Issued from inline assembly on purpose: through the compiler
-  // builtin every LDS read that follows waits for ALL outstanding loads (the compiler cannot
-  // tell the ring slots apart), which would undo the multi-stage pipeline.  The kernel keeps
-  // its own count instead (s_waitcnt vmcnt(n) before the workgroup barrier).
+  // Request one k-step's slab.  rs: buffer resource whose base is the slab's first element minus
+  // BIAS bytes and whose num_records is the number of valid bytes from the slab's first element
+  // plus BIAS (BIAS itself = nothing to read); LDS_OFF: byte offset of the tile in LDS (ring slot
+  // and operand; a constant); wave_off = wave * NI * 1024.  Issued from inline assembly on
+  // purpose: through the compiler builtin every LDS read that follows waits for ALL outstanding
+  // loads (the compiler cannot tell the ring slots apart), which would undo the multi-stage
+  // pipeline.  The kernel keeps its own count instead (s_waitcnt vmcnt(n) before the barrier).
   template <int LDS_OFF>
   __device__ __forceinline__ void load(int4v rs, int wave_off) const {
     // uniform already; this only tells the compiler so (no instruction when it is in SGPRs)
@@ -153,18 +162,32 @@ struct OperandTile {
     // Two hazards the hardware does not interlock and the compiler cannot see inside an asm
     // block (CDNA3 ISA guide, manually inserted wait states): a scalar write of the resource
     // registers needs 5 wait states before a vector-memory instruction reads them (the compiler
-    // assembles the 4-register tuple right before the first block: s_nop 4), and a scalar write
-    // of M0 needs 1 before the LDS-direct load that uses it (s_nop 0).
-    asm volatile("s_nop 4\n\ts_add_u32 m0, %0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds"
-                 :
-                 : "s"(wave_off), "i"(LDS_OFF), "v"(voff[0]), "s"(rs)
-                 : "memory", "m0", "scc");
+    // assembles the 4-register tuple right before the block: s_nop 4), and a scalar write of M0
+    // needs 1 before the LDS-direct load that uses it (s_nop 0).  One block per group, so that
+    // nothing the compiler emits can come between the M0 write and its loads.
 #pragma unroll
-    for (int j = 1; j < NI; ++j)
-      asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds"
-                   :
-                   : "s"(wave_off), "i"(LDS_OFF + j * NW * 1024), "v"(voff[j]), "s"(rs)
-                   : "memory", "m0", "scc");
+    for (int g0 = 0; g0 < NI; g0 += GROUP) {
+      if constexpr (GROUP == 4) {
+        asm volatile(
+            "s_nop 4\n\ts_add_u32 m0, %0, %1\n\ts_nop 0\n\t"
+            "buffer_load_dwordx4 %2, %6, 0 offen lds\n\t"
+            "buffer_load_dwordx4 %3, %6, 0 offen offset:1024 lds\n\t"
+            "buffer_load_dwordx4 %4, %6, 0 offen offset:2048 lds\n\t"
+            "buffer_load_dwordx4 %5, %6, 0 offen offset:3072 lds"
+            :
+            : "s"(wave_off), "i"(LDS_OFF + g0 * 1024), "v"(voff[g0]), "v"(voff[g0 + 1]), "v"(voff[g0 + 2]),
+              "v"(voff[g0 + 3]), "s"(rs)
+            : "memory", "m0", "scc");
+      } else {
+        asm volatile(
+            "s_nop 4\n\ts_add_u32 m0, %0, %1\n\ts_nop 0\n\t"
+            "buffer_load_dwordx4 %2, %4, 0 offen lds\n\t"
+            "buffer_load_dwordx4 %3, %4, 0 offen offset:1024 lds"
+            :
+            : "s"(wave_off), "i"(LDS_OFF + g0 * 1024), "v"(voff[g0]), "v"(voff[g0 + 1]), "s"(rs)
+            : "memory", "m0", "scc");
+      }
+    }
   }
 };
 
@@ -278,7 +301,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   FragAddr<BN, BKS, NI> fb;
   fa.init(wm0, lane);
   fb.init(wn0, lane);
-  const int wave_off = wave * 1024;
+  const int wave_off_a = wave * TA::NI * 1024, wave_off_b = wave * TB::NI * 1024;
 
   // Global cursors, all in scalar registers: one buffer resource per operand whose base is
   // the first element of the next k-step's slab and whose num_records is what may still be
@@ -293,14 +316,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
     rs[1] = (int)(uint32_t)(p >> 32);  // a device address has no bits above 47: stride and swizzle fields stay 0
   };
   auto get_base = [](const int4v& rs) { return ((uint64_t)(uint32_t)rs[1] << 32) | (uint32_t)rs[0]; };
-  set_base(ars, (uint64_t)Ab);
-  set_base(brs, (uint64_t)Bb);
+  set_base(ars, (uint64_t)Ab - TA::BIAS);
+  set_base(brs, (uint64_t)Bb - TB::BIAS);
   ars[0] = __builtin_amdgcn_readfirstlane(ars[0]);
   ars[1] = __builtin_amdgcn_readfirstlane(ars[1]);
   brs[0] = __builtin_amdgcn_readfirstlane(brs[0]);
   brs[1] = __builtin_amdgcn_readfirstlane(brs[1]);
-  ars[2] = __builtin_amdgcn_readfirstlane((int)a_ext);
-  brs[2] = __builtin_amdgcn_readfirstlane((int)b_ext);
+  // record counts carry the operand tiles' BIAS (see OperandTile); BIAS alone = nothing readable
+  const int a_rec0 = (int)a_ext + TA::BIAS, b_rec0 = (int)b_ext + TB::BIAS;
+  ars[2] = __builtin_amdgcn_readfirstlane(a_rec0);
+  brs[2] = __builtin_amdgcn_readfirstlane(b_rec0);
   ars[3] = brs[3] = (int)BUF_RSRC_FLAGS;
   // Branch-free on purpose: with control flow inside the k-loop the accumulators get
   // copied between register files at every merge point.
@@ -312,15 +337,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
     set_base(ars, get_base(ars) + (uint64_t)(cross ? a_jump : (long)a_step));
     set_base(brs, get_base(brs) + (uint64_t)(cross ? b_jump : (long)b_step));
     // past the last k-tile the cursor reads nothing: such a request fills its slot with zeros
-    ars[2] = more ? (cross ? (int)a_ext : max(ars[2] - a_step, 0)) : 0;
-    brs[2] = more ? (cross ? (int)b_ext : max(brs[2] - b_step, 0)) : 0;
+    ars[2] = more ? (cross ? a_rec0 : max(ars[2] - a_step, (int)TA::BIAS)) : (int)TA::BIAS;
+    brs[2] = more ? (cross ? b_rec0 : max(brs[2] - b_step, (int)TB::BIAS)) : (int)TB::BIAS;
     seg_left = cross ? tiles_per_seg : seg_left;
   };
   // request the next k-tile into ring slot S
   auto issue_loads = [&](auto S) {
     constexpr int off = decltype(S)::value * CFG::STAGE_ELEMS * 2;
-    ta.template load<off>(ars, wave_off);
-    tb.template load<off + TA::LDS_BYTES>(brs, wave_off);
+    ta.template load<off>(ars, wave_off_a);
+    tb.template load<off + TA::LDS_BYTES>(brs, wave_off_b);
     advance();
   };
 
@@ -587,7 +612,7 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
     const int kv = g.k_valid > 0 ? g.k_valid : g.K, mv = g.m_valid > 0 ? g.m_valid : g.M, nv = g.n_valid > 0 ? g.n_valid : g.N;
     const long a_ext = g.a_kstrided ? ((long)(kv - 1) * g.lda + mv) * 2 : ((long)(mv - 1) * g.lda + g.kseg_len) * 2;
     const long b_ext = g.b_kstrided ? ((long)(kv - 1) * g.ldb + nv) * 2 : ((long)(nv - 1) * g.ldb + g.kseg_len) * 2;
-    if (a_ext > 0x7fffffffL || b_ext > 0x7fffffffL) return false;
+    if (a_ext > 0x7fffffffL - 4096 || b_ext > 0x7fffffffL - 4096) return false;
     if ((long)BK * g.lda * 2 > 0x7fffffffL || (long)BK * g.ldb * 2 > 0x7fffffffL) return false;
   }
   if ((g.epi & (EPI_ADD | EPI_MUL)) && (g.ldaux % 4 || !aligned_to(g.aux, 16))) return false;
