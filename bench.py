@@ -27,7 +27,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 # rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in profiles/gemm_mfma_bert_large_pmc_traffic.md,
 # each counter scaled by what it reads for the library's copy kernel of known size (1.990 / 1.000).
 # Counters cannot be read from inside this process, so the figure is carried here per workload.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"bert_large": 64767955}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"bert_large": 64959596}
 
 
 def stage_flops(cfg, M):
