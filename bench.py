@@ -99,6 +99,16 @@ def main():
     theta = I.make_params(cfg, seed)
     mbs = [I.make_microbatch(cfg, seed, m) for m in range(M)]
 
+    def make_io(r):
+        emb, head = cfg.has_embedding, cfg.has_mlm_head
+        xs = [r.to_dev(mb["ids"].reshape(T).astype(np.int32)) if emb else r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+        dys = None if head else [r.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
+        auxs = [r.to_dev(mb["targets"].reshape(T).astype(np.int32)) for mb in mbs] if head else None
+        ys = [torch.zeros(1, dtype=torch.float32, device="cuda") if head else r.empty_act() for _ in range(M)]
+        dxs = None if emb else [r.empty_act() for _ in range(M)]
+        ptr = lambda ts: None if ts is None else [t.data_ptr() for t in ts]
+        return xs, dys, ys, dxs, auxs, (ptr(xs), ptr(dys), ptr(ys), ptr(dxs), ptr(auxs))
+
     results = {}
     peak_bytes = {}
     runner = None
@@ -108,14 +118,7 @@ def main():
                                             ("early_backward_recompute", B.ORDER_EARLY_BACKWARD, K, B.FLAG_RECOMPUTE),
                                             ("early_backward", B.ORDER_EARLY_BACKWARD, K, 0)):
         r = B.StageRunner(c_config(cfg, slots, flags=flags), theta)
-        emb, head = cfg.has_embedding, cfg.has_mlm_head
-        xs = [r.to_dev(mb["ids"].reshape(T).astype(np.int32)) if emb else r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
-        dys = None if head else [r.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
-        auxs = [r.to_dev(mb["targets"].reshape(T).astype(np.int32)) for mb in mbs] if head else None
-        ys = [torch.zeros(1, dtype=torch.float32, device="cuda") if head else r.empty_act() for _ in range(M)]
-        dxs = None if emb else [r.empty_act() for _ in range(M)]
-        ptr = lambda ts: None if ts is None else [t.data_ptr() for t in ts]
-        px, pdy, py, pdx, paux = ptr(xs), ptr(dys), ptr(ys), ptr(dxs), ptr(auxs)
+        xs, dys, ys, dxs, auxs, (px, pdy, py, pdx, paux) = make_io(r)
 
         def step():
             B.stage_zero_grads(r.h)
@@ -141,6 +144,31 @@ def main():
             r.close()
             del r
             torch.cuda.empty_cache()
+
+    # the early-backward iteration again as ONE HIP graph (captured once on a stream of its own, then
+    # replayed): what is left when the host issues one launch per iteration instead of one per kernel
+    with torch.cuda.stream(torch.cuda.Stream()):
+        rg = B.StageRunner(c_config(cfg, K), theta)
+        gio = make_io(rg)
+        gp = gio[-1]
+        B.stage_zero_grads(rg.h)
+        B.stage_run_schedule(rg.h, M, K, B.ORDER_EARLY_BACKWARD, gp[0], gp[1], gp[2], gp[3], gp[4])
+        B.stage_sync(rg.h)
+        B.stage_graph_capture(rg.h, M, K, B.ORDER_EARLY_BACKWARD, gp[0], gp[1], gp[2], gp[3], gp[4], zero_grads_first=True)
+        for _ in range(args.warmup):
+            B.stage_graph_launch(rg.h)
+        B.stage_sync(rg.h)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            B.stage_graph_launch(rg.h)
+        B.stage_sync(rg.h)
+        torch.cuda.synchronize()
+        results["graph"] = (time.perf_counter() - t0) / args.steps
+        del gio
+        rg.close()
+        del rg
+    torch.cuda.empty_cache()
 
     # per-kernel-class times: the same steps again with HIP events around every launch
     r, step = runner
@@ -201,6 +229,8 @@ def main():
                       "throughput_vs_stored": sec / results["early_backward_recompute"],
                       "memory_vs_stored": peak_bytes["early_backward_recompute"] / peak_bytes["early_backward"],
                       "memory_vs_gpipe_order": peak_bytes["early_backward_recompute"] / peak_bytes["gpipe"]},
+        "hip_graph_replay": {"samples_per_s": M * cfg.micro_batch / results["graph"], "ms_per_step": results["graph"] * 1e3,
+                             "note": "one hipGraphLaunch per iteration (one backward lane inside the graph)"},
         "apply_adam": {"ms": apply_ms, "params": int(r.sizes.n_params), "bytes": int(apply_bytes),
                        "GB/s": apply_bytes / (apply_ms * 1e-3) / 1e9, "hbm_peak_frac": apply_bytes / (apply_ms * 1e-3) / 8e12},
         "kernel_classes": classes,

@@ -158,6 +158,24 @@ int stage_run_schedule(stage_handle h, int M, int K, int order,
                        void* const* ys, void* const* dxs, const void* const* auxs,
                        const int32_t* explicit_ops, int n_ops);
 
+/* The same iteration as ONE HIP graph: stage_graph_capture records what stage_run_schedule would
+ * enqueue (all of the library's streams, forked from and joined back into the caller's stream;
+ * with zero_grads_first != 0 preceded by stage_zero_grads) and instantiates it; stage_graph_launch
+ * replays it on the caller's stream at the cost of one launch call.  The device pointers of the
+ * capture are baked in.  Requirements: the stage's stream is not the default (NULL) stream; the
+ * same iteration ran eagerly once before (the kernels' launch attributes are set on their first
+ * eager launch); no micro-batch is resident; per-launch timing is off.  The graph holds no memset
+ * node (accumulators and buffers are cleared by kernels).  A new capture replaces the old one;
+ * stage_destroy frees it.  Task and launch counters advance per replay as if run eagerly.
+ * The captured iteration uses one backward lane (results are the same bits either way), and a
+ * replay has measured no faster than the eager lanes: this pair is for callers that need the
+ * iteration as one launchable object. */
+int stage_graph_capture(stage_handle h, int M, int K, int order,
+                        const void* const* xs, const void* const* dys,
+                        void* const* ys, void* const* dxs, const void* const* auxs,
+                        const int32_t* explicit_ops, int n_ops, int zero_grads_first);
+int stage_graph_launch(stage_handle h);
+
 /* Device pointer to the fp32 accumulators (aliases the arena; valid until
  * stage_destroy) and their element count. */
 int stage_grads(stage_handle h, void** grads_dev, uint64_t* n);

@@ -63,6 +63,8 @@ SYMBOLS = {
     "stage_bwd": (_i, [_vp, _i, _vp, _vp]),
     "stage_schedule_ops": (_i, [_i, _i, _i, C.POINTER(C.c_int32), _i]),
     "stage_run_schedule": (_i, [_vp, _i, _i, _i, _pp, _pp, _pp, _pp, _pp, C.POINTER(C.c_int32), _i]),
+    "stage_graph_capture": (_i, [_vp, _i, _i, _i, _pp, _pp, _pp, _pp, _pp, C.POINTER(C.c_int32), _i, _i]),
+    "stage_graph_launch": (_i, [_vp]),
     "stage_grads": (_i, [_vp, C.POINTER(_vp), C.POINTER(C.c_uint64)]),
     "stage_zero_grads": (_i, [_vp]),
     "stage_apply_adam": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _f, _f, _f, _f, _f, _i]),
@@ -165,6 +167,20 @@ def stage_run_schedule(h, M, K, order, xs=None, dys=None, ys=None, dxs=None, aux
         ops, n = (C.c_int32 * max(len(enc), 1))(*enc), len(enc)
     _check(load().stage_run_schedule(h, M, K, order, _ptr_array(xs, M), _ptr_array(dys, M), _ptr_array(ys, M),
                                      _ptr_array(dxs, M), _ptr_array(auxs, M), ops, n))
+
+
+def stage_graph_capture(h, M, K, order, xs=None, dys=None, ys=None, dxs=None, auxs=None, explicit_ops=None,
+                        zero_grads_first=True):
+    ops, n = None, 0
+    if explicit_ops is not None:
+        enc = [(m + 1) if k == "F" else -(m + 1) for k, m in explicit_ops]
+        ops, n = (C.c_int32 * max(len(enc), 1))(*enc), len(enc)
+    _check(load().stage_graph_capture(h, M, K, order, _ptr_array(xs, M), _ptr_array(dys, M), _ptr_array(ys, M),
+                                      _ptr_array(dxs, M), _ptr_array(auxs, M), ops, n, int(zero_grads_first)))
+
+
+def stage_graph_launch(h):
+    _check(load().stage_graph_launch(h))
 
 
 def stage_grads(h):

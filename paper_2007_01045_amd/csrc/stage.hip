@@ -229,6 +229,12 @@ struct dapple_stage {
   hipStream_t fwd = nullptr;   // library-owned: forward tasks inside stage_run_schedule
   hipStream_t bwd2 = nullptr;  // library-owned: every second backward task inside stage_run_schedule
   hipEvent_t ev_b2done = nullptr;
+  hipGraph_t graph = nullptr;          // a captured iteration (stage_graph_capture)
+  hipGraphExec_t graph_exec = nullptr;
+  uint64_t graph_fwd = 0, graph_bwd = 0, graph_launches = 0;
+  int graph_peak = 0;
+  bool capturing = false;              // inside stage_graph_capture
+  bool ran_eagerly = false;            // kernels' attributes are set on their first eager launch
   hipStream_t cur = nullptr;   // where the task being enqueued puts its main-line kernels (st or fwd)
   std::vector<hipEvent_t> ev_f, ev_b;  // per slot: forward done (fwd lane), backward done (caller's stream)
   hipEvent_t ev_start = nullptr;
@@ -263,13 +269,15 @@ struct dapple_stage {
   // side -> main, in two halves: mark the side work of a layer done; later make main wait for it
   int side_done(int layer) {
     if (dry) return STAGE_OK;
-    if (hipEventRecord(ev[layer * 6 + 4], side) != hipSuccess || hipEventRecord(ev[layer * 6 + 5], side2) != hipSuccess)
+    if (hipEventRecord(ev[layer * 6 + 4], side) != hipSuccess ||
+        (side2 != side && hipEventRecord(ev[layer * 6 + 5], side2) != hipSuccess))
       return fail(STAGE_E_DEVICE, "event record failed");
     return STAGE_OK;
   }
   int join(int layer) {
     if (dry) return STAGE_OK;
-    if (hipStreamWaitEvent(cur, ev[layer * 6 + 4], 0) != hipSuccess || hipStreamWaitEvent(cur, ev[layer * 6 + 5], 0) != hipSuccess)
+    if (hipStreamWaitEvent(cur, ev[layer * 6 + 4], 0) != hipSuccess ||
+        (side2 != side && hipStreamWaitEvent(cur, ev[layer * 6 + 5], 0) != hipSuccess))
       return fail(STAGE_E_DEVICE, "event wait failed");
     return STAGE_OK;
   }
@@ -786,6 +794,8 @@ int stage_destroy(stage_handle h) {
     if (h->fwd) (void)hipStreamSynchronize(h->fwd);
     if (h->bwd2) (void)hipStreamSynchronize(h->bwd2);
   }
+  if (h->graph_exec) (void)hipGraphExecDestroy(h->graph_exec);
+  if (h->graph) (void)hipGraphDestroy(h->graph);
   for (auto& e : h->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
   for (auto& e : h->ev) (void)hipEventDestroy(e);
   for (auto& e : h->ev_f) (void)hipEventDestroy(e);
@@ -910,15 +920,17 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
   // B_{j+1} overlaps the tail of B_j.  Their accumulator updates still happen in list order: all of
   // them are issued, in host order, on the one side stream.  (A first or last stage also
   // accumulates on its backward stream -- embedding tables, head -- and keeps one backward lane.)
+  // A capture keeps to one backward lane: the HIP runtime that ships with PyTorch 2.10 (ROCm 7.0) recurses
+  // without end in hipStreamEndCapture once two streams other than the capture's origin have waited for each
+  // other's events (side lane <-> second backward lane); the origin may wait for and be waited for by anyone.
   static const int bwd_lanes_env = envi("DAPPLE_BWD_LANES");
   const bool two = lanes && !strict && h->L.ws_copies == 2 && !h->cfg.has_embedding && !h->cfg.has_mlm_head &&
-                   !h->no_side && bwd_lanes_env != 1;
+                   !h->no_side && bwd_lanes_env != 1 && !h->capturing;
   int n_bwd = 0;
   bool used_b2 = false;
   if (lanes) {
     TRY(hip_ok(hipEventRecord(h->ev_start, h->st)));
     TRY(hip_ok(hipStreamWaitEvent(h->fwd, h->ev_start, 0)));
-    if (two) TRY(hip_ok(hipStreamWaitEvent(h->bwd2, h->ev_start, 0)));
   }
   int rc = STAGE_OK;
   for (int32_t op : ops) {
@@ -943,6 +955,10 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
       hipStream_t bs = second ? h->bwd2 : h->st;
       ++n_bwd;
       if (lanes) {
+        if (second && !used_b2) {
+          if ((rc = hip_ok(hipStreamWaitEvent(bs, h->ev_start, 0))) != STAGE_OK) break;
+          used_b2 = true;
+        }
         s = find_slot(h, m);
         int w = strict ? last_f_slot : s;
         if (w >= 0 && (rc = hip_ok(hipStreamWaitEvent(bs, h->ev_f[w], 0))) != STAGE_OK) break;
@@ -953,7 +969,6 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
       h->cur = h->st;
       h->ws_shift = 0;
       if (rc != STAGE_OK) break;
-      used_b2 = used_b2 || second;
       if (lanes) {
         if ((rc = hip_ok(hipEventRecord(h->ev_b[s], bs))) != STAGE_OK) break;
         b_pending[s] = 1;
@@ -970,7 +985,53 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
     if (rc2 == STAGE_OK) rc2 = hip_ok(hipStreamWaitEvent(h->st, h->ev_b2done, 0));
     if (rc == STAGE_OK) rc = rc2;
   }
+  if (rc == STAGE_OK && !h->dry) h->ran_eagerly = true;
   return rc;
+}
+
+int stage_graph_capture(stage_handle h, int M, int K, int order, const void* const* xs, const void* const* dys,
+                        void* const* ys, void* const* dxs, const void* const* auxs, const int32_t* explicit_ops,
+                        int n_ops, int zero_grads_first) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  if (h->dry) return fail(STAGE_E_CONFIG, "a dry-run stage launches nothing to capture");
+  if (!h->st) return fail(STAGE_E_CONFIG, "the stage was created on the default (NULL) stream, which cannot be captured");
+  if (h->profiling) return fail(STAGE_E_CONFIG, "switch per-launch timing off before capturing");
+  if (!h->ran_eagerly)
+    return fail(STAGE_E_BAD_ORDER, "run the same iteration once with stage_run_schedule before capturing it");
+  if (h->live != 0) return fail(STAGE_E_BAD_ORDER, "%d micro-batches are still resident", h->live);
+  if (h->graph_exec) { (void)hipGraphExecDestroy(h->graph_exec); h->graph_exec = nullptr; }
+  if (h->graph) { (void)hipGraphDestroy(h->graph); h->graph = nullptr; }
+  const uint64_t f0 = h->fwd_tasks, b0 = h->bwd_tasks, l0 = h->launches;
+  if (hipStreamBeginCapture(h->st, hipStreamCaptureModeThreadLocal) != hipSuccess)
+    return fail(STAGE_E_DEVICE, "hipStreamBeginCapture failed");
+  int rc = STAGE_OK;
+  h->capturing = true;
+  if (zero_grads_first) rc = stage_zero_grads(h);
+  if (rc == STAGE_OK) rc = stage_run_schedule(h, M, K, order, xs, dys, ys, dxs, auxs, explicit_ops, n_ops);
+  h->capturing = false;
+  hipGraph_t g = nullptr;
+  hipError_t e = hipStreamEndCapture(h->st, &g);   // always: the stream must leave capture mode
+  h->graph_fwd = h->fwd_tasks - f0; h->graph_bwd = h->bwd_tasks - b0; h->graph_launches = h->launches - l0;
+  h->fwd_tasks = f0; h->bwd_tasks = b0; h->launches = l0;   // captured, not run
+  if (rc != STAGE_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
+  if (e != hipSuccess || !g) return fail(STAGE_E_DEVICE, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+  h->graph = g;
+  e = hipGraphInstantiate(&h->graph_exec, g, nullptr, nullptr, 0);
+  if (e != hipSuccess) {
+    h->graph_exec = nullptr;
+    return fail(STAGE_E_DEVICE, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+  }
+  return STAGE_OK;
+}
+
+int stage_graph_launch(stage_handle h) {
+  if (!h) return fail(STAGE_E_NULL, "handle is NULL");
+  if (!h->graph_exec) return fail(STAGE_E_BAD_ORDER, "no captured iteration: call stage_graph_capture first");
+  if (h->live != 0) return fail(STAGE_E_BAD_ORDER, "%d micro-batches are still resident", h->live);
+  hipError_t e = hipGraphLaunch(h->graph_exec, h->st);
+  if (e != hipSuccess) return fail(STAGE_E_DEVICE, "hipGraphLaunch failed: %s", hipGetErrorString(e));
+  h->fwd_tasks += h->graph_fwd; h->bwd_tasks += h->graph_bwd; h->launches += h->graph_launches;
+  return STAGE_OK;
 }
 
 int stage_grads(stage_handle h, void** grads_dev, uint64_t* n) {

@@ -279,3 +279,68 @@ def test_lanes_do_not_change_a_bit_for_any_depth(M, K):
         assert np.array_equal(a["ys"][m], b["ys"][m]) and np.array_equal(a["dxs"][m], b["dxs"][m])
         assert np.array_equal(a["dxs"][m], c["dxs"][m])
     assert a["stats"]["peak_live"] == min(K, M) and b["stats"]["peak_live"] == M
+
+
+def test_graph_replays_equal_the_eager_iteration_bitwise():
+    # one HIP graph of the whole iteration (all lanes): replayed several times with eager work and
+    # synchronisations in between, every replay must reproduce the eager result
+    import torch
+    cfg = I.StageConfig(3, 256, 4, 512, 128, 2, 5, 2, "bf16")
+    M, K = 5, 2
+    theta, mbs = make_inputs(cfg, SEED, M)
+    eager = run_gpu(cfg, theta, mbs, M, K, B.ORDER_EARLY_BACKWARD)
+    T, H = cfg.tokens, cfg.hidden
+    with torch.cuda.stream(torch.cuda.Stream()):
+        r = B.StageRunner(c_config(cfg, K), theta)
+        try:
+            xs = [r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+            dys = [r.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
+            ys = [r.empty_act() for _ in range(M)]
+            dxs = [r.empty_act() for _ in range(M)]
+            ptr = lambda ts: [t.data_ptr() for t in ts]
+            args = (r.h, M, K, B.ORDER_EARLY_BACKWARD, ptr(xs), ptr(dys), ptr(ys), ptr(dxs))
+            with pytest.raises(B.StageError) as e:          # nothing ran eagerly yet
+                B.stage_graph_capture(*args)
+            assert e.value.code == B.STAGE_E_BAD_ORDER
+            with pytest.raises(B.StageError):               # nothing captured yet
+                B.stage_graph_launch(r.h)
+            B.stage_run_schedule(*args)
+            B.stage_sync(r.h)
+            B.stage_graph_capture(*args, zero_grads_first=True)
+            for rep in range(3):
+                for t in ys + dxs:
+                    t.zero_()                               # eager work between the replays
+                r.grads.fill_(float(rep + 1))               # the graph clears the accumulators itself
+                B.stage_graph_launch(r.h)
+                B.stage_sync(r.h)
+                torch.cuda.synchronize()
+                assert np.array_equal(r.grads.cpu().numpy(), eager["grads"]), rep
+                for m in range(M):
+                    assert np.array_equal(to_np(ys[m]), eager["ys"][m]) and np.array_equal(to_np(dxs[m]), eager["dxs"][m])
+                # an eager iteration in between still works and agrees
+                B.stage_zero_grads(r.h)
+                B.stage_run_schedule(*args)
+                B.stage_sync(r.h)
+                assert np.array_equal(r.grads.cpu().numpy(), eager["grads"])
+            st = B.stage_stats(r.h)
+            assert st.fwd_tasks == 7 * M and st.bwd_tasks == 7 * M and st.live_slots == 0
+        finally:
+            r.close()
+
+
+def test_graph_capture_needs_a_real_stream():
+    cfg = I.CONFIGS["tiny"]
+    theta, mbs = make_inputs(cfg, SEED, 2)
+    r = B.StageRunner(c_config(cfg, 2), theta)     # torch's default stream is the NULL stream
+    try:
+        T, H = cfg.tokens, cfg.hidden
+        xs = [r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+        ys = [r.empty_act() for _ in range(2)]
+        ptr = lambda ts: [t.data_ptr() for t in ts]
+        B.stage_run_schedule(r.h, 2, 2, B.ORDER_EARLY_BACKWARD, ptr(xs), ptr(xs), ptr(ys), ptr(ys))
+        B.stage_sync(r.h)
+        with pytest.raises(B.StageError) as e:
+            B.stage_graph_capture(r.h, 2, 2, B.ORDER_EARLY_BACKWARD, ptr(xs), ptr(xs), ptr(ys), ptr(ys))
+        assert e.value.code == B.STAGE_E_CONFIG
+    finally:
+        r.close()
