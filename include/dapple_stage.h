@@ -176,6 +176,10 @@ int stage_graph_capture(stage_handle h, int M, int K, int order,
                         const int32_t* explicit_ops, int n_ops, int zero_grads_first);
 int stage_graph_launch(stage_handle h);
 
+/* The stream the stage was created on, and a copy of its configuration. */
+int stage_stream(stage_handle h, void** hip_stream_out);
+int stage_get_config(stage_handle h, stage_config* cfg_out);
+
 /* Device pointer to the fp32 accumulators (aliases the arena; valid until
  * stage_destroy) and their element count. */
 int stage_grads(stage_handle h, void** grads_dev, uint64_t* n);

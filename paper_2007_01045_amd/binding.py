@@ -65,6 +65,8 @@ SYMBOLS = {
     "stage_run_schedule": (_i, [_vp, _i, _i, _i, _pp, _pp, _pp, _pp, _pp, C.POINTER(C.c_int32), _i]),
     "stage_graph_capture": (_i, [_vp, _i, _i, _i, _pp, _pp, _pp, _pp, _pp, C.POINTER(C.c_int32), _i, _i]),
     "stage_graph_launch": (_i, [_vp]),
+    "stage_stream": (_i, [_vp, C.POINTER(_vp)]),
+    "stage_get_config": (_i, [_vp, C.POINTER(stage_config)]),
     "stage_grads": (_i, [_vp, C.POINTER(_vp), C.POINTER(C.c_uint64)]),
     "stage_zero_grads": (_i, [_vp]),
     "stage_apply_adam": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _f, _f, _f, _f, _f, _i]),
@@ -76,6 +78,15 @@ SYMBOLS = {
     "stage_sync": (_i, [_vp]),
     "stage_destroy": (_i, [_vp]),
     "stage_last_error": (C.c_char_p, []),
+    "pipeline_warmup_depths": (_i, [_i, _i, _i, _i, C.POINTER(C.c_int32)]),
+    "pipeline_partition_stream_create": (_i, [_i, _i, C.POINTER(_vp)]),
+    "pipeline_partition_stream_destroy": (_i, [_vp]),
+    "pipeline_boundary_bytes": (C.c_size_t, [_i, _i, C.c_size_t]),
+    "pipeline_create": (_i, [C.POINTER(_vp), _i, C.POINTER(_vp), _vp, C.c_size_t, C.c_size_t, _i]),
+    "pipeline_destroy": (_i, [_vp]),
+    "pipeline_run": (_i, [_vp, _i, C.POINTER(C.c_int32), _i, _pp, _pp, _pp, _pp, _pp]),
+    "pipeline_sync": (_i, [_vp]),
+    "pipeline_timeline": (_i, [_vp, C.POINTER(C.c_double), C.POINTER(C.c_double), _i]),
     "dapple_gemm": (_i, [_i, C.POINTER(dapple_gemm_desc), _vp]),
     "dapple_attention_fwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "dapple_attention_bwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
@@ -94,6 +105,11 @@ def load():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2007_01045_amd.build` "
                                "(there is no fallback path)")
+        # PyTorch brings its own copy of the HIP runtime.  The library shares streams and device memory
+        # with it, so both must sit on the same copy: with torch loaded first, the dynamic linker gives
+        # ours the runtime that is already there; loaded the other way round the process would hold two
+        # runtimes, and the second one finds no device.
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SYMBOLS.items():
             fn = getattr(lib, name)
@@ -181,6 +197,72 @@ def stage_graph_capture(h, M, K, order, xs=None, dys=None, ys=None, dxs=None, au
 
 def stage_graph_launch(h):
     _check(load().stage_graph_launch(h))
+
+
+def stage_stream(h):
+    p = C.c_void_p()
+    _check(load().stage_stream(h, C.byref(p)))
+    return p.value
+
+
+def stage_get_config(h) -> stage_config:
+    c = stage_config()
+    _check(load().stage_get_config(h, C.byref(c)))
+    return c
+
+
+POLICY_A, POLICY_B = 0, 1
+
+
+def pipeline_warmup_depths(S, M, policy=POLICY_A, D=0):
+    buf = (C.c_int32 * max(S, 1))()
+    _check(load().pipeline_warmup_depths(S, M, policy, D, buf))
+    return list(buf[:S])
+
+
+def pipeline_partition_stream_create(part, nparts):
+    p = C.c_void_p()
+    _check(load().pipeline_partition_stream_create(part, nparts, C.byref(p)))
+    return p.value
+
+
+def pipeline_partition_stream_destroy(stream):
+    _check(load().pipeline_partition_stream_destroy(stream))
+
+
+def pipeline_boundary_bytes(S, max_M, act_bytes):
+    return load().pipeline_boundary_bytes(S, max_M, act_bytes)
+
+
+def pipeline_create(stage_handles, boundary_ptr, boundary_bytes, act_bytes, max_M):
+    S = len(stage_handles)
+    arr = (C.c_void_p * S)(*[h.value if isinstance(h, C.c_void_p) else h for h in stage_handles])
+    out = C.c_void_p()
+    _check(load().pipeline_create(C.byref(out), S, arr, boundary_ptr, boundary_bytes, act_bytes, max_M))
+    return out
+
+
+def pipeline_destroy(p):
+    _check(load().pipeline_destroy(p))
+
+
+def pipeline_run(p, M, K, order, xs, dys=None, auxs=None, ys=None, dxs=None):
+    Ka = None if K is None else (C.c_int32 * len(K))(*K)
+    _check(load().pipeline_run(p, M, Ka, order, _ptr_array(xs, M), _ptr_array(dys, M), _ptr_array(auxs, M),
+                               _ptr_array(ys, M), _ptr_array(dxs, M)))
+
+
+def pipeline_sync(p):
+    _check(load().pipeline_sync(p))
+
+
+def pipeline_timeline(p, S, M):
+    """{(kind, stage, m): (start_ms, end_ms)} of the last run, kind 'F' or 'B'."""
+    n = 2 * S * M
+    a, b = (C.c_double * n)(), (C.c_double * n)()
+    _check(load().pipeline_timeline(p, a, b, n))
+    return {(("F", "B")[k], i, m): (a[(k * S + i) * M + m], b[(k * S + i) * M + m])
+            for k in range(2) for i in range(S) for m in range(M)}
 
 
 def stage_grads(h):
@@ -274,7 +356,7 @@ class StageRunner:
     """Owns the device buffers of one stage (weights, arena, per-micro-batch inputs
     and outputs) as torch tensors and passes their addresses to the library."""
 
-    def __init__(self, cfg: stage_config, theta_f32, device="cuda:0"):
+    def __init__(self, cfg: stage_config, theta_f32, device="cuda:0", stream_ptr=None):
         import torch
         load()
         self.torch, self.cfg, self.device = torch, cfg, device
@@ -286,7 +368,8 @@ class StageRunner:
         self.arena = torch.empty(self.sizes.arena_bytes + 256, dtype=torch.uint8, device=device)
         base = self.arena.data_ptr()
         self.arena_ptr = (base + 255) // 256 * 256
-        self.stream = torch.cuda.current_stream(device)
+        # stream_ptr: a raw hipStream_t (a partition stream of the pipeline); else torch's current stream
+        self.stream = torch.cuda.current_stream(device) if stream_ptr is None else torch.cuda.ExternalStream(stream_ptr)
         self.h = stage_init(cfg, self.weights.data_ptr(), self.arena_ptr, self.sizes.arena_bytes,
                             self.stream.cuda_stream)
         off = self.arena_ptr - base

@@ -10,7 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdapple_stage.so")
-SOURCES = ["gemm.hip", "attention.hip", "rowops.hip", "embed_head.hip", "optimizer.hip", "stage.hip", "kernel_api.hip"]
+SOURCES = ["gemm.hip", "attention.hip", "rowops.hip", "embed_head.hip", "optimizer.hip", "stage.hip", "pipeline.hip", "kernel_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result", "-Wno-inline-asm",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -146,4 +146,11 @@ hipError_t launch_mul(Dtype dt, const void* a, const void* b, void* c, long n, h
 hipError_t launch_adam(Dtype dt, float* G, float* w32, float* m, float* v, void* w, size_t n, float lr, float beta1,
                        float beta2, float eps, float c1, float c2, float grad_scale, int zero_grads, hipStream_t st);
 
+// ---------------------------------------------------------------- host-side plumbing shared by the C-ABI files
+// records the message stage_last_error() returns and hands the code back
+int set_error(int code, const char* fmt, ...);
+// the compute-unit mask of a stream made by pipeline_partition_stream_create (NULL for any other stream);
+// n_words receives its length in 32-bit words
+const uint32_t* partition_mask_of(hipStream_t st, int* n_words);
+
 }  // namespace dapple

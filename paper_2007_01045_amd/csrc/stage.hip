@@ -33,6 +33,15 @@ int fail(int code, const char* fmt, ...) {
   return code;
 }
 
+// a library-owned lane next to the caller's stream: on the same compute units when the caller's stream is one of
+// the partitions of pipeline_partition_stream_create, an ordinary non-blocking stream otherwise
+hipError_t make_lane(hipStream_t like, hipStream_t* out) {
+  int n = 0;
+  const uint32_t* mask = partition_mask_of(like, &n);
+  if (mask) return hipExtStreamCreateWithCUMask(out, (uint32_t)n, mask);
+  return hipStreamCreateWithFlags(out, hipStreamNonBlocking);
+}
+
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 enum KClass {
@@ -683,6 +692,18 @@ static int validate_ops(const int32_t* ops, int n, int M, int limit) {
 }
 
 // ------------------------------------------------------------------ C ABI
+namespace dapple {
+int set_error(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+}  // namespace dapple
+
 extern "C" {
 
 const char* stage_last_error(void) { return g_err.c_str(); }
@@ -741,23 +762,25 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
     if (h->no_side) {
       h->side = h->side2 = h->st;
     } else {
-      if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) {
+      hipError_t e = make_lane(h->st, &h->side);
+      if (e != hipSuccess) {
         delete h;
-        return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
+        return fail(STAGE_E_DEVICE, "creating the side stream failed: %s", hipGetErrorString(e));
       }
       // one side stream by default: a second one (DAPPLE_SIDE_LANES=2) takes more from the backward
       // lanes than it gives (measured 1957 against 2108 samples/s on the BERT-Large-shaped stage)
       if (envi("DAPPLE_SIDE_LANES") != 2) {
         h->side2 = h->side;
-      } else if (hipStreamCreateWithFlags(&h->side2, hipStreamNonBlocking) != hipSuccess) {
+      } else if (make_lane(h->st, &h->side2) != hipSuccess) {
         delete h;
         return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
       }
     }
-    if (hipStreamCreateWithFlags(&h->fwd, hipStreamNonBlocking) != hipSuccess ||
-        hipStreamCreateWithFlags(&h->bwd2, hipStreamNonBlocking) != hipSuccess) {
+    hipError_t e = make_lane(h->st, &h->fwd);
+    if (e == hipSuccess) e = make_lane(h->st, &h->bwd2);
+    if (e != hipSuccess) {
       delete h;
-      return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
+      return fail(STAGE_E_DEVICE, "creating the forward / second backward stream failed: %s", hipGetErrorString(e));
     }
     h->ev.resize((size_t)cfg->n_layers * 6);
     h->ev_f.resize(cfg->max_slots);
@@ -1031,6 +1054,18 @@ int stage_graph_launch(stage_handle h) {
   hipError_t e = hipGraphLaunch(h->graph_exec, h->st);
   if (e != hipSuccess) return fail(STAGE_E_DEVICE, "hipGraphLaunch failed: %s", hipGetErrorString(e));
   h->fwd_tasks += h->graph_fwd; h->bwd_tasks += h->graph_bwd; h->launches += h->graph_launches;
+  return STAGE_OK;
+}
+
+int stage_stream(stage_handle h, void** hip_stream_out) {
+  if (!h || !hip_stream_out) return fail(STAGE_E_NULL, "handle and hip_stream_out must not be NULL");
+  *hip_stream_out = (void*)h->st;
+  return STAGE_OK;
+}
+
+int stage_get_config(stage_handle h, stage_config* cfg_out) {
+  if (!h || !cfg_out) return fail(STAGE_E_NULL, "handle and cfg_out must not be NULL");
+  *cfg_out = h->cfg;
   return STAGE_OK;
 }
 

@@ -1,0 +1,169 @@
+"""S stages on one GPU run as a pipeline through the C-ABI of dapple_pipeline.h: results against the
+float64 oracle of the unsplit model and against the single-stage HIP path, residency per stage,
+and the measured timeline against the dependences of the schedule."""
+import numpy as np
+import pytest
+
+from oracle import pipeline_oracle as PO
+from stage_util import *  # noqa: F401,F403
+
+pytestmark = pytest.mark.gpu
+
+SEED = 20200701
+TOL_F32, TOL_BF16 = 1e-4, 2e-2
+
+
+class Pipe:
+    """S equal stages cut from one L-layer configuration, each on a stream of its own (a partition of the
+    compute units when parts > 1), with the boundary buffer between them."""
+
+    def __init__(self, cfg, S, slots, theta, max_M, parts=1):
+        import torch
+        assert cfg.n_layers % S == 0
+        self.torch, self.S, self.cfg = torch, S, cfg
+        self.part_cfg = I.StageConfig(cfg.n_layers // S, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch,
+                                      cfg.M, cfg.K, cfg.dtype, ln_eps=cfg.ln_eps)
+        n = I.n_params(self.part_cfg)
+        assert n * S == theta.size
+        self.streams, self.runners, self.p = [], [], None
+        for i in range(S):
+            self.streams.append(B.pipeline_partition_stream_create(i if parts > 1 else 0, parts))
+            self.runners.append(B.StageRunner(c_config(self.part_cfg, slots[i]), theta[i * n:(i + 1) * n],
+                                              stream_ptr=self.streams[i]))
+        E = 2 if cfg.dtype == "bf16" else 4
+        self.act_bytes = cfg.tokens * cfg.hidden * E
+        nb = B.pipeline_boundary_bytes(S, max_M, self.act_bytes)
+        self.boundary = torch.zeros(nb + 256, dtype=torch.uint8, device="cuda")
+        bp = (self.boundary.data_ptr() + 255) // 256 * 256
+        torch.cuda.synchronize()
+        self.p = B.pipeline_create([r.h for r in self.runners], bp, nb, self.act_bytes, max_M)
+
+    def run(self, M, K, order, mbs):
+        torch, r0, cfg = self.torch, self.runners[0], self.cfg
+        T, H = cfg.tokens, cfg.hidden
+        xs = [r0.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+        dys = [r0.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
+        ys = [r0.empty_act() for _ in range(M)]
+        dxs = [r0.empty_act() for _ in range(M)]
+        for r in self.runners:
+            B.stage_zero_grads(r.h)
+            B.stage_reset_stats(r.h)
+        torch.cuda.synchronize()
+        ptr = lambda ts: [t.data_ptr() for t in ts]
+        B.pipeline_run(self.p, M, K, order, ptr(xs), ptr(dys), None, ptr(ys), ptr(dxs))
+        B.pipeline_sync(self.p)
+        torch.cuda.synchronize()
+        return dict(ys=[to_np(y) for y in ys], dxs=[to_np(d) for d in dxs],
+                    grads=np.concatenate([r.grads.cpu().numpy() for r in self.runners]),
+                    peak=[B.stage_stats(r.h).peak_live_slots for r in self.runners],
+                    timeline=B.pipeline_timeline(self.p, self.S, M))
+
+    def close(self):
+        if self.p is not None:
+            B.pipeline_destroy(self.p)
+        for r in self.runners:
+            r.close()
+        for s in self.streams:
+            B.pipeline_partition_stream_destroy(s)
+
+
+def check_timeline(tl, S, M, lists):
+    """Every dependence of the schedule shows in the measured times: a stage's tasks in list order, a forward after
+    the forward of the stage before, a backward after the backward of the stage behind."""
+    eps = 1e-3   # ms: an event pair on one stream can read equal
+    for i in range(S):
+        prev = None
+        for kind, m in lists[i]:
+            t0, t1 = tl[(kind, i, m)]
+            assert t1 >= t0 >= 0
+            if prev is not None:
+                assert t0 >= prev - eps, (kind, i, m)
+            prev = t1
+            if kind == "F" and i > 0:
+                assert t0 >= tl[("F", i - 1, m)][1] - eps
+            if kind == "B":
+                dep = ("F", i, m) if i == S - 1 else ("B", i + 1, m)
+                assert t0 >= tl[dep][1] - eps
+
+
+@pytest.mark.parametrize("parts", [1, 3])
+def test_three_stages_fp32_equal_the_single_stage_bitwise(parts):
+    cfg = I.StageConfig(6, 64, 4, 128, 16, 2, 5, 3, "f32", ln_eps=1e-5)
+    S, M = 3, 5
+    theta, mbs = make_inputs(cfg, SEED, M)
+    K = B.pipeline_warmup_depths(S, M, B.POLICY_A)
+    assert K == [3, 2, 1] == PO.warmup_depths(S, M, "A")
+    one = run_gpu(cfg, theta, mbs, M, 3, B.ORDER_EARLY_BACKWARD)
+    pipe = Pipe(cfg, S, K, theta, M, parts)
+    try:
+        got = pipe.run(M, K, B.ORDER_EARLY_BACKWARD, mbs)
+        again = pipe.run(M, K, B.ORDER_EARLY_BACKWARD, mbs)
+    finally:
+        pipe.close()
+    assert got["peak"] == K                      # stage i never holds more than K_i = S - i micro-batches
+    assert np.array_equal(got["grads"], one["grads"]) and np.array_equal(again["grads"], one["grads"])
+    for m in range(M):
+        assert np.array_equal(got["ys"][m], one["ys"][m]) and np.array_equal(got["dxs"][m], one["dxs"][m])
+    st, ref = run_oracle(cfg, theta, mbs, M, 3)
+    compare(cfg, st, ref, got, TOL_F32, M)
+    check_timeline(got["timeline"], S, M, PO.stage_lists(S, M, K))
+
+
+def test_gpipe_order_and_policy_b_give_the_same_bits_with_more_residents():
+    cfg = I.StageConfig(4, 64, 4, 128, 16, 2, 6, 3, "f32", ln_eps=1e-5)
+    S, M = 2, 6
+    theta, mbs = make_inputs(cfg, SEED, M)
+    KA, KB = B.pipeline_warmup_depths(S, M, B.POLICY_A), B.pipeline_warmup_depths(S, M, B.POLICY_B)
+    assert KA == [2, 1] and KB == [3, 1] == PO.warmup_depths(S, M, "B")
+    pipe = Pipe(cfg, S, [M, M], theta, M)
+    try:
+        a = pipe.run(M, KA, B.ORDER_EARLY_BACKWARD, mbs)
+        b = pipe.run(M, KB, B.ORDER_EARLY_BACKWARD, mbs)
+        g = pipe.run(M, None, B.ORDER_GPIPE, mbs)
+        check_timeline(g["timeline"], S, M, PO.stage_lists(S, M, None, PO.GPIPE))
+        assert a["peak"] == KA and b["peak"] == KB and g["peak"] == [M, M]
+        assert np.array_equal(a["grads"], b["grads"]) and np.array_equal(a["grads"], g["grads"])
+        # depths that grow along the pipeline deadlock: refused before anything is enqueued
+        with pytest.raises(B.StageError) as e:
+            pipe.run(M, [1, 2], B.ORDER_EARLY_BACKWARD, mbs)
+        assert e.value.code == B.STAGE_E_BAD_ORDER
+        with pytest.raises(B.StageError):
+            pipe.run(M + 1, KA, B.ORDER_EARLY_BACKWARD, mbs + mbs[:1])     # more than max_M
+        c = pipe.run(M, KA, B.ORDER_EARLY_BACKWARD, mbs)                   # still usable afterwards
+        assert np.array_equal(a["grads"], c["grads"])
+    finally:
+        pipe.close()
+
+
+def test_four_bf16_stages_on_four_partitions_follow_the_oracle():
+    cfg = I.StageConfig(4, 256, 4, 512, 128, 2, 6, 4, "bf16")
+    S, M = 4, 6
+    theta, mbs = make_inputs(cfg, SEED, M)
+    K = B.pipeline_warmup_depths(S, M, B.POLICY_A)
+    pipe = Pipe(cfg, S, K, theta, M, parts=4)
+    try:
+        got = pipe.run(M, K, B.ORDER_EARLY_BACKWARD, mbs)
+    finally:
+        pipe.close()
+    assert got["peak"] == [4, 3, 2, 1]
+    st, ref = run_oracle(cfg, theta, mbs, M, 4)
+    compare(cfg, st, ref, got, TOL_BF16, M)
+    check_timeline(got["timeline"], S, M, PO.stage_lists(S, M, K))
+
+
+def test_pipeline_create_error_paths():
+    cfg = I.StageConfig(2, 64, 4, 128, 16, 2, 2, 2, "f32", ln_eps=1e-5)
+    theta, _ = make_inputs(cfg, SEED, 2)
+    r = B.StageRunner(c_config(cfg, 2), theta)          # on torch's default (NULL) stream
+    try:
+        import torch
+        buf = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+        with pytest.raises(B.StageError) as e:
+            B.pipeline_create([r.h], buf.data_ptr(), buf.numel(), cfg.tokens * cfg.hidden * 4, 2)
+        assert e.value.code == B.STAGE_E_CONFIG            # no stream of its own
+    finally:
+        r.close()
+    with pytest.raises(B.StageError):
+        B.pipeline_partition_stream_create(3, 3)
+    with pytest.raises(B.StageError):
+        B.pipeline_warmup_depths(0, 4)

@@ -15,12 +15,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared(header):
     txt = open(os.path.join(ROOT, "include", header)).read()
     txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
-    return set(re.findall(r"\b((?:stage|dapple)_[a-z0-9_]+)\s*\(", txt))
+    return set(re.findall(r"\b((?:stage|dapple|pipeline)_[a-z0-9_]+)\s*\(", txt))
 
 
 def test_library_exports_every_declared_symbol():
     lib = B.load()
-    names = _declared("dapple_stage.h") | _declared("dapple_kernels.h")
+    names = _declared("dapple_stage.h") | _declared("dapple_kernels.h") | _declared("dapple_pipeline.h")
     assert len(names) >= 20
     for n in names:
         assert hasattr(lib, n), n
