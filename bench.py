@@ -68,6 +68,60 @@ def cpu_baseline(cfg, seed, M_sample, K_sample):
                       f"{dt:.1f} s", "tflops": stage_flops(cfg, M_sample) / dt / 1e12}
 
 
+def pipeline_study(cfg, seed, S=4, layers_per_stage=3, M=16):
+    """S stages of the workload's layer shape run as a pipeline on S equal partitions of the compute units
+    (one virtual device each): task times F_i, B_i alone, the latency model from them, and the measured
+    iteration in the early-backward order (K_i = S - i) and in the GPipe order (all M resident)."""
+    import numpy as np
+    import torch
+
+    from paper_2007_01045_amd import binding as B
+    from paper_2007_01045_amd import inputs as I
+    from tests.stage_util import c_config
+
+    part = I.StageConfig(layers_per_stage, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, M, S, cfg.dtype,
+                         ln_eps=cfg.ln_eps, name="pipeline_part")
+    T, H = part.tokens, part.hidden
+    K = B.pipeline_warmup_depths(S, M, B.POLICY_A)
+    pr = B.PipelineRunner([c_config(part, M, flags=B.FLAG_ONE_STREAM) for _ in range(S)],
+                          [I.make_params(part, seed + i) for i in range(S)], M, parts=S)
+    try:
+        r0 = pr.runners[0]
+        mbs = [I.make_microbatch(part, seed, m) for m in range(M)]
+        xs = [r0.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+        dys = [r0.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
+        ys = [r0.empty_act() for _ in range(M)]
+        dxs = [r0.empty_act() for _ in range(M)]
+        torch.cuda.synchronize()
+
+        def once(m, k, order):
+            pr.run(m, k, order, xs[:m], dys[:m], None, ys[:m], dxs[:m])
+            tl = pr.timeline(m)
+            dur = {key: v[1] - v[0] for key, v in tl.items()}
+            return max(v[1] for v in tl.values()), dur
+
+        alone = [once(1, [1] * S, B.ORDER_EARLY_BACKWARD)[1] for _ in range(8)][3:]
+        F = [float(np.median([d[("F", i, 0)] for d in alone])) for i in range(S)]
+        Bt = [float(np.median([d[("B", i, 0)] for d in alone])) for i in range(S)]
+        out = {"stages": S, "layers_per_stage": layers_per_stage, "M": M, "K": K, "compute_units_per_stage": 256 // S,
+               "F_ms_alone": F, "B_ms_alone": Bt, "pivot_stage": B.pipeline_pivot_stage(M, F, Bt),
+               "model_ms_from_alone": B.pipeline_latency_model(M, F, Bt)}
+        for name, order, k in (("early_backward", B.ORDER_EARLY_BACKWARD, K), ("gpipe_order", B.ORDER_GPIPE, None)):
+            runs = [once(M, k, order) for _ in range(4)][1:]
+            span, dur = sorted(runs, key=lambda r: r[0])[len(runs) // 2]
+            Fi = [float(np.mean([dur[("F", i, m)] for m in range(M)])) for i in range(S)]
+            Bi = [float(np.mean([dur[("B", i, m)] for m in range(M)])) for i in range(S)]
+            busy = [M * (Fi[i] + Bi[i]) for i in range(S)]
+            out[name] = {"measured_ms": span, "model_ms_from_in_situ_task_times": B.pipeline_latency_model(M, Fi, Bi),
+                         "F_ms_in_situ": Fi, "B_ms_in_situ": Bi, "bubble_frac_per_stage": [1.0 - b / span for b in busy],
+                         "peak_resident": [int(B.stage_stats(r.h).peak_live_slots) for r in pr.runners]}
+            for r in pr.runners:
+                B.stage_reset_stats(r.h)
+        return out
+    finally:
+        pr.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,6 +129,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="bert_large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-pipeline", action="store_true")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -235,6 +290,8 @@ def main():
                        "GB/s": apply_bytes / (apply_ms * 1e-3) / 1e9, "hbm_peak_frac": apply_bytes / (apply_ms * 1e-3) / 8e12},
         "kernel_classes": classes,
     }
+    if not args.no_pipeline and not cfg.has_embedding and not cfg.has_mlm_head:
+        out["pipeline_on_partitions"] = pipeline_study(cfg, seed)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, seed, 2, 2)
     print(json.dumps(out))

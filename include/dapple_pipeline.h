@@ -37,6 +37,15 @@ enum { PIPELINE_POLICY_A = 0, PIPELINE_POLICY_B = 1 };
  * above M nor below 1; D <= 0 means "memory holds all M".  Host only. */
 int pipeline_warmup_depths(int S, int M, int policy, int D, int32_t* K_out);
 
+/* The planner's estimate of one iteration (section IV-A, equations 1 and 2) with the AllReduce term
+ * at zero: L = T_w + T_s + T_e, T_w = sum_{s<=Q} F_s, T_s = (M-1)(F_Q + B_Q), T_e = sum_{a<=Q} B_a
+ * (the maximum of equation 1 without AllReduce; the pivot's own last backward counts into the
+ * ending phase).  F, B: S forward / backward task times; Q: the pivot stage, or -1 for the rule of
+ * section IV-B-1 (start at the last stage, move to an earlier stage s when (M-1)(F_s+B_s) exceeds
+ * (M-1)(F_Q+B_Q) plus the work of the stages between).  Host only. */
+int pipeline_pivot_stage(int S, int M, const double* F, const double* B);
+int pipeline_latency_model(int S, int M, const double* F, const double* B, int Q, double* L_out);
+
 /* A stream that may only use compute units [part*n/nparts, (part+1)*n/nparts) of the n the
  * device has (nparts = 1: all of them): one of nparts virtual devices.  Default priority.
  * Create the stage of that virtual device with this stream; destroy the stage first. */

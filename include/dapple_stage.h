@@ -74,13 +74,17 @@ enum { STAGE_DTYPE_F32 = 0, STAGE_DTYPE_BF16 = 1 };
 enum {
   STAGE_FLAG_DRY_RUN = 1,   /* host bookkeeping only: no kernel is launched and device pointers may
                                be NULL (for CPU-side tests) */
-  STAGE_FLAG_RECOMPUTE = 2  /* re-computation (section VI-E, Table VI's "+ RC" rows): a resident
+  STAGE_FLAG_RECOMPUTE = 2, /* re-computation (section VI-E, Table VI's "+ RC" rows): a resident
                                micro-batch keeps only the stage's input (token ids on a first stage)
                                and its targets; stage_bwd re-runs the forward from them before it goes
                                backward.  slot_bytes shrinks to that; two activation buffers of the
                                full size (one for the forward tasks, one for the backward tasks) are
                                part of workspace_bytes.  Gradients and outputs are bit-identical to
                                the stage without the flag. */
+  STAGE_FLAG_ONE_STREAM = 4 /* every kernel goes on the stage's own stream: no library-owned lanes.
+                               For a stage that is one of several run beside each other
+                               (dapple_pipeline.h), where the overlap comes from the other stages and
+                               every extra hardware queue costs.  Same bits as without the flag. */
 };
 
 typedef struct {

@@ -21,6 +21,7 @@ ORDER_GPIPE, ORDER_EARLY_BACKWARD, ORDER_EXPLICIT = 0, 1, 2
 DTYPE_F32, DTYPE_BF16 = 0, 1
 FLAG_DRY_RUN = 1
 FLAG_RECOMPUTE = 2
+FLAG_ONE_STREAM = 4
 EPI_BIAS, EPI_ADD, EPI_MUL, EPI_GELU, EPI_ACC32 = 1, 2, 4, 8, 16
 
 
@@ -79,6 +80,8 @@ SYMBOLS = {
     "stage_destroy": (_i, [_vp]),
     "stage_last_error": (C.c_char_p, []),
     "pipeline_warmup_depths": (_i, [_i, _i, _i, _i, C.POINTER(C.c_int32)]),
+    "pipeline_pivot_stage": (_i, [_i, _i, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "pipeline_latency_model": (_i, [_i, _i, C.POINTER(C.c_double), C.POINTER(C.c_double), _i, C.POINTER(C.c_double)]),
     "pipeline_partition_stream_create": (_i, [_i, _i, C.POINTER(_vp)]),
     "pipeline_partition_stream_destroy": (_i, [_vp]),
     "pipeline_boundary_bytes": (C.c_size_t, [_i, _i, C.c_size_t]),
@@ -218,6 +221,18 @@ def pipeline_warmup_depths(S, M, policy=POLICY_A, D=0):
     buf = (C.c_int32 * max(S, 1))()
     _check(load().pipeline_warmup_depths(S, M, policy, D, buf))
     return list(buf[:S])
+
+
+def pipeline_pivot_stage(M, F, B):
+    S = len(F)
+    return _check(load().pipeline_pivot_stage(S, M, (C.c_double * S)(*F), (C.c_double * S)(*B)))
+
+
+def pipeline_latency_model(M, F, B, Q=-1):
+    S = len(F)
+    out = C.c_double()
+    _check(load().pipeline_latency_model(S, M, (C.c_double * S)(*F), (C.c_double * S)(*B), Q, C.byref(out)))
+    return out.value
 
 
 def pipeline_partition_stream_create(part, nparts):
@@ -414,3 +429,49 @@ class StageRunner:
         if self.h is not None:
             stage_destroy(self.h)
             self.h = None
+
+
+class PipelineRunner:
+    """S stages on one GPU tied into a pipeline (dapple_pipeline.h): owns the stage runners, their streams
+    (one partition of the compute units each when parts > 1, ordinary torch streams when parts == 0)
+    and the boundary buffer."""
+
+    def __init__(self, cfgs, thetas, max_M, parts=1, device="cuda:0"):
+        import torch
+        load()
+        self.torch, self.S, self.max_M = torch, len(cfgs), max_M
+        self.streams, self.tstreams, self.runners, self.p = [], [], [], None
+        for i, (cfg, th) in enumerate(zip(cfgs, thetas)):
+            if parts == 0:
+                self.tstreams.append(torch.cuda.Stream(device))
+                sp = self.tstreams[-1].cuda_stream
+            else:
+                self.streams.append(pipeline_partition_stream_create(i if parts > 1 else 0, parts))
+                sp = self.streams[-1]
+            self.runners.append(StageRunner(cfg, th, device, stream_ptr=sp))
+        c = cfgs[0]
+        self.act_bytes = c.micro_batch * c.seq * c.hidden * (2 if c.dtype == DTYPE_BF16 else 4)
+        nb = pipeline_boundary_bytes(self.S, max_M, self.act_bytes)
+        self.boundary = torch.zeros(nb + 256, dtype=torch.uint8, device=device)
+        torch.cuda.synchronize()
+        self.p = pipeline_create([r.h for r in self.runners], (self.boundary.data_ptr() + 255) // 256 * 256, nb,
+                                 self.act_bytes, max_M)
+
+    def run(self, M, K, order, xs, dys=None, auxs=None, ys=None, dxs=None):
+        """Enqueue one iteration (device tensors in, device tensors written) and wait for it."""
+        ptr = lambda ts: None if ts is None else [t.data_ptr() for t in ts]
+        pipeline_run(self.p, M, K, order, ptr(xs), ptr(dys), ptr(auxs), ptr(ys), ptr(dxs))
+        pipeline_sync(self.p)
+
+    def timeline(self, M):
+        return pipeline_timeline(self.p, self.S, M)
+
+    def close(self):
+        if self.p is not None:
+            pipeline_destroy(self.p)
+            self.p = None
+        for r in self.runners:
+            r.close()
+        for s in self.streams:
+            pipeline_partition_stream_destroy(s)
+        self.streams = []

@@ -63,6 +63,31 @@ int pipeline_warmup_depths(int S, int M, int policy, int D, int32_t* K_out) {
   return STAGE_OK;
 }
 
+int pipeline_pivot_stage(int S, int M, const double* F, const double* B) {
+  if (!F || !B) return set_error(STAGE_E_NULL, "F and B must not be NULL");
+  if (S < 1 || M < 1) return set_error(STAGE_E_BAD_ORDER, "S and M must be positive (S=%d, M=%d)", S, M);
+  int Q = S - 1;
+  for (int s = S - 2; s >= 0; --s) {
+    double between = 0.0;
+    for (int a = s + 1; a < Q; ++a) between += F[a] + B[a];
+    if ((M - 1) * (F[s] + B[s]) > (M - 1) * (F[Q] + B[Q]) + between) Q = s;
+  }
+  return Q;
+}
+
+int pipeline_latency_model(int S, int M, const double* F, const double* B, int Q, double* L_out) {
+  if (!F || !B || !L_out) return set_error(STAGE_E_NULL, "F, B and L_out must not be NULL");
+  if (S < 1 || M < 1) return set_error(STAGE_E_BAD_ORDER, "S and M must be positive (S=%d, M=%d)", S, M);
+  if (Q < 0) Q = pipeline_pivot_stage(S, M, F, B);
+  if (Q >= S) return set_error(STAGE_E_BAD_ORDER, "pivot stage %d of %d", Q, S);
+  double Tw = 0.0, Te = 0.0;
+  for (int s = 0; s <= Q; ++s) Tw += F[s];
+  // without AllReduce the maximum over s is taken at s = 0: every backward from the pivot down to stage 0
+  for (int a = 0; a <= Q; ++a) Te += B[a];
+  *L_out = Tw + (M - 1) * (F[Q] + B[Q]) + Te;
+  return STAGE_OK;
+}
+
 int pipeline_partition_stream_create(int part, int nparts, void** hip_stream_out) {
   if (!hip_stream_out) return set_error(STAGE_E_NULL, "hip_stream_out must not be NULL");
   if (nparts < 1 || part < 0 || part >= nparts) return set_error(STAGE_E_CONFIG, "part %d of %d", part, nparts);

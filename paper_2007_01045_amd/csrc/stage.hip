@@ -756,8 +756,8 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
     {
       const char* e = getenv("DAPPLE_SERIAL");   // 1: no side lane and no forward lane; 2: no forward lane; 3: no side lane
       int v = e ? atoi(e) : 0;
-      h->serial = v == 1 || v == 2;
-      h->no_side = v == 1 || v == 3;
+      h->serial = v == 1 || v == 2 || (cfg->flags & STAGE_FLAG_ONE_STREAM);
+      h->no_side = v == 1 || v == 3 || (cfg->flags & STAGE_FLAG_ONE_STREAM);
     }
     if (h->no_side) {
       h->side = h->side2 = h->st;
@@ -776,12 +776,8 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
         return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
       }
     }
-    hipError_t e = make_lane(h->st, &h->fwd);
-    if (e == hipSuccess) e = make_lane(h->st, &h->bwd2);
-    if (e != hipSuccess) {
-      delete h;
-      return fail(STAGE_E_DEVICE, "creating the forward / second backward stream failed: %s", hipGetErrorString(e));
-    }
+    // the forward lane and the second backward lane are made by the first stage_run_schedule that uses lanes:
+    // a stage driven task by task (stage_fwd / stage_bwd, the pipeline of several stages) holds no idle queues
     h->ev.resize((size_t)cfg->n_layers * 6);
     h->ev_f.resize(cfg->max_slots);
     h->ev_b.resize(cfg->max_slots);
@@ -799,10 +795,11 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
   }
   h->cur = h->st;
   int rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->grads, h->L.grad_bytes, q); });
-  if (rc == STAGE_OK && cfg->has_mlm_head)
+  if (rc == STAGE_OK && cfg->has_mlm_head) {
     rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->ws(h->L.wh_info), 16, q); });
     if (rc == STAGE_OK && h->L.recompute)
       rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->ws(h->L.wh_info2), 16, q); });
+  }
   if (rc != STAGE_OK) { delete h; return rc; }
   *out = h;
   return STAGE_OK;
@@ -900,6 +897,14 @@ int stage_schedule_ops(int M, int K, int order, int32_t* ops_out, int capacity) 
   return (int)ops.size();
 }
 
+static int ensure_lanes(stage_handle h) {
+  if (h->fwd) return STAGE_OK;
+  hipError_t e = make_lane(h->st, &h->fwd);
+  if (e == hipSuccess) e = make_lane(h->st, &h->bwd2);
+  if (e != hipSuccess) return fail(STAGE_E_DEVICE, "creating the forward / second backward stream failed: %s", hipGetErrorString(e));
+  return STAGE_OK;
+}
+
 int stage_run_schedule(stage_handle h, int M, int K, int order, const void* const* xs, const void* const* dys,
                        void* const* ys, void* const* dxs, const void* const* auxs, const int32_t* explicit_ops,
                        int n_ops) {
@@ -951,6 +956,7 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
                    !h->no_side && bwd_lanes_env != 1 && !h->capturing;
   int n_bwd = 0;
   bool used_b2 = false;
+  if (lanes) TRY(ensure_lanes(h));
   if (lanes) {
     TRY(hip_ok(hipEventRecord(h->ev_start, h->st)));
     TRY(hip_ok(hipStreamWaitEvent(h->fwd, h->ev_start, 0)));
@@ -1024,6 +1030,7 @@ int stage_graph_capture(stage_handle h, int M, int K, int order, const void* con
   if (h->live != 0) return fail(STAGE_E_BAD_ORDER, "%d micro-batches are still resident", h->live);
   if (h->graph_exec) { (void)hipGraphExecDestroy(h->graph_exec); h->graph_exec = nullptr; }
   if (h->graph) { (void)hipGraphDestroy(h->graph); h->graph = nullptr; }
+  if (!h->serial) TRY(ensure_lanes(h));   // no stream is created inside a capture
   const uint64_t f0 = h->fwd_tasks, b0 = h->bwd_tasks, l0 = h->launches;
   if (hipStreamBeginCapture(h->st, hipStreamCaptureModeThreadLocal) != hipSuccess)
     return fail(STAGE_E_DEVICE, "hipStreamBeginCapture failed");
@@ -1133,7 +1140,7 @@ int stage_profile_read(stage_handle h, int n, uint64_t* launches, double* ms, do
   if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess ||
                   hipStreamSynchronize(h->side2) != hipSuccess))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
-  if (!h->dry && h->fwd && (hipStreamSynchronize(h->fwd) != hipSuccess || hipStreamSynchronize(h->bwd2) != hipSuccess))
+  if (!h->dry && h->fwd && (hipStreamSynchronize(h->fwd) != hipSuccess || (h->bwd2 && hipStreamSynchronize(h->bwd2) != hipSuccess)))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
   for (int i = 0; i < n; ++i) { launches[i] = 0; ms[i] = 0; flops[i] = 0; }
   if (const char* path = getenv("DAPPLE_TIMELINE")) {

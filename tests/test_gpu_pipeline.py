@@ -15,28 +15,19 @@ TOL_F32, TOL_BF16 = 1e-4, 2e-2
 
 class Pipe:
     """S equal stages cut from one L-layer configuration, each on a stream of its own (a partition of the
-    compute units when parts > 1), with the boundary buffer between them."""
+    compute units when parts > 1, an ordinary stream when parts == 0), with the boundary buffer between them."""
 
-    def __init__(self, cfg, S, slots, theta, max_M, parts=1):
+    def __init__(self, cfg, S, slots, theta, max_M, parts=1, flags=0):
         import torch
         assert cfg.n_layers % S == 0
         self.torch, self.S, self.cfg = torch, S, cfg
-        self.part_cfg = I.StageConfig(cfg.n_layers // S, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch,
-                                      cfg.M, cfg.K, cfg.dtype, ln_eps=cfg.ln_eps)
-        n = I.n_params(self.part_cfg)
+        part = I.StageConfig(cfg.n_layers // S, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch,
+                             cfg.M, cfg.K, cfg.dtype, ln_eps=cfg.ln_eps)
+        n = I.n_params(part)
         assert n * S == theta.size
-        self.streams, self.runners, self.p = [], [], None
-        for i in range(S):
-            self.streams.append(B.pipeline_partition_stream_create(i if parts > 1 else 0, parts))
-            self.runners.append(B.StageRunner(c_config(self.part_cfg, slots[i]), theta[i * n:(i + 1) * n],
-                                              stream_ptr=self.streams[i]))
-        E = 2 if cfg.dtype == "bf16" else 4
-        self.act_bytes = cfg.tokens * cfg.hidden * E
-        nb = B.pipeline_boundary_bytes(S, max_M, self.act_bytes)
-        self.boundary = torch.zeros(nb + 256, dtype=torch.uint8, device="cuda")
-        bp = (self.boundary.data_ptr() + 255) // 256 * 256
-        torch.cuda.synchronize()
-        self.p = B.pipeline_create([r.h for r in self.runners], bp, nb, self.act_bytes, max_M)
+        self.pr = B.PipelineRunner([c_config(part, slots[i], flags=flags) for i in range(S)],
+                                   [theta[i * n:(i + 1) * n] for i in range(S)], max_M, parts)
+        self.runners = self.pr.runners
 
     def run(self, M, K, order, mbs):
         torch, r0, cfg = self.torch, self.runners[0], self.cfg
@@ -49,22 +40,15 @@ class Pipe:
             B.stage_zero_grads(r.h)
             B.stage_reset_stats(r.h)
         torch.cuda.synchronize()
-        ptr = lambda ts: [t.data_ptr() for t in ts]
-        B.pipeline_run(self.p, M, K, order, ptr(xs), ptr(dys), None, ptr(ys), ptr(dxs))
-        B.pipeline_sync(self.p)
+        self.pr.run(M, K, order, xs, dys, None, ys, dxs)
         torch.cuda.synchronize()
         return dict(ys=[to_np(y) for y in ys], dxs=[to_np(d) for d in dxs],
                     grads=np.concatenate([r.grads.cpu().numpy() for r in self.runners]),
                     peak=[B.stage_stats(r.h).peak_live_slots for r in self.runners],
-                    timeline=B.pipeline_timeline(self.p, self.S, M))
+                    timeline=self.pr.timeline(M))
 
     def close(self):
-        if self.p is not None:
-            B.pipeline_destroy(self.p)
-        for r in self.runners:
-            r.close()
-        for s in self.streams:
-            B.pipeline_partition_stream_destroy(s)
+        self.pr.close()
 
 
 def check_timeline(tl, S, M, lists):
@@ -86,7 +70,7 @@ def check_timeline(tl, S, M, lists):
                 assert t0 >= tl[dep][1] - eps
 
 
-@pytest.mark.parametrize("parts", [1, 3])
+@pytest.mark.parametrize("parts", [0, 1, 3])
 def test_three_stages_fp32_equal_the_single_stage_bitwise(parts):
     cfg = I.StageConfig(6, 64, 4, 128, 16, 2, 5, 3, "f32", ln_eps=1e-5)
     S, M = 3, 5
@@ -135,12 +119,13 @@ def test_gpipe_order_and_policy_b_give_the_same_bits_with_more_residents():
         pipe.close()
 
 
-def test_four_bf16_stages_on_four_partitions_follow_the_oracle():
+@pytest.mark.parametrize("flags", [0, B.FLAG_ONE_STREAM])
+def test_four_bf16_stages_on_four_partitions_follow_the_oracle(flags):
     cfg = I.StageConfig(4, 256, 4, 512, 128, 2, 6, 4, "bf16")
     S, M = 4, 6
     theta, mbs = make_inputs(cfg, SEED, M)
     K = B.pipeline_warmup_depths(S, M, B.POLICY_A)
-    pipe = Pipe(cfg, S, K, theta, M, parts=4)
+    pipe = Pipe(cfg, S, K, theta, M, parts=4, flags=flags)
     try:
         got = pipe.run(M, K, B.ORDER_EARLY_BACKWARD, mbs)
     finally:
@@ -148,7 +133,13 @@ def test_four_bf16_stages_on_four_partitions_follow_the_oracle():
     assert got["peak"] == [4, 3, 2, 1]
     st, ref = run_oracle(cfg, theta, mbs, M, 4)
     compare(cfg, st, ref, got, TOL_BF16, M)
-    check_timeline(got["timeline"], S, M, PO.stage_lists(S, M, K))
+    tl = got["timeline"]
+    check_timeline(tl, S, M, PO.stage_lists(S, M, K))
+    # the stages really ran beside each other: the iteration is shorter than its tasks laid end to end,
+    # and no shorter than the busiest stage
+    span = max(v[1] for v in tl.values())
+    busy = [sum(tl[(k, i, m)][1] - tl[(k, i, m)][0] for k in "FB" for m in range(M)) for i in range(S)]
+    assert max(busy) <= span * 1.001 and span < sum(busy)
 
 
 def test_pipeline_create_error_paths():

@@ -344,3 +344,13 @@ def test_graph_capture_needs_a_real_stream():
         assert e.value.code == B.STAGE_E_CONFIG
     finally:
         r.close()
+
+
+def test_one_stream_flag_changes_no_bit():
+    cfg = I.StageConfig(3, 256, 4, 512, 128, 2, 5, 2, "bf16")
+    theta, mbs = make_inputs(cfg, SEED, 5)
+    a = run_gpu(cfg, theta, mbs, 5, 2, B.ORDER_EARLY_BACKWARD)
+    b = run_gpu(cfg, theta, mbs, 5, 2, B.ORDER_EARLY_BACKWARD, flags=B.FLAG_ONE_STREAM)
+    assert np.array_equal(a["grads"], b["grads"])
+    for m in range(5):
+        assert np.array_equal(a["ys"][m], b["ys"][m]) and np.array_equal(a["dxs"][m], b["dxs"][m])

@@ -173,3 +173,25 @@ def test_null_handle_and_error_text():
     with pytest.raises(B.StageError) as e:
         B.stage_fwd(None, 0, None, None)
     assert e.value.code == B.STAGE_E_NULL and "NULL" in str(e.value)
+
+
+def test_pipeline_host_functions_follow_the_oracle():
+    import random
+    from oracle import pipeline_oracle as PO
+    rng = random.Random(7)
+    for _ in range(300):
+        S, M = rng.randint(1, 6), rng.randint(1, 12)
+        F = [rng.uniform(0.2, 3.0) for _ in range(S)]
+        Bt = [rng.uniform(0.2, 6.0) for _ in range(S)]
+        if rng.random() < 0.3:
+            F[0] *= 4; Bt[0] *= 4
+        assert B.pipeline_pivot_stage(M, F, Bt) == PO.pivot_stage(F, Bt, M)
+        assert B.pipeline_latency_model(M, F, Bt) == pytest.approx(PO.latency_model(F, Bt, M), rel=1e-13)
+        Q = rng.randrange(S)
+        assert B.pipeline_latency_model(M, F, Bt, Q) == pytest.approx(PO.latency_model(F, Bt, M, Q), rel=1e-13)
+        for pol, name in ((B.POLICY_A, "A"), (B.POLICY_B, "B")):
+            D = rng.choice([0, 1, 2, 5, 100])
+            assert B.pipeline_warmup_depths(S, M, pol, D) == PO.warmup_depths(S, M, name, None if D == 0 else D)
+    with pytest.raises(B.StageError):
+        B.pipeline_latency_model(3, [1.0, 1.0], [1.0, 1.0], Q=2)
+    assert B.pipeline_boundary_bytes(3, 4, 1000) == 2 * 2 * 4 * 1024
