@@ -293,7 +293,7 @@ def main():
     if not args.no_pipeline and not cfg.has_embedding and not cfg.has_mlm_head:
         out["pipeline_on_partitions"] = pipeline_study(cfg, seed)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, seed, 2, 2)
+        out["cpu_baseline"] = cpu_baseline(cfg, seed, min(4, M), 2)
     print(json.dumps(out))
 
 
