@@ -27,7 +27,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 # rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in profiles/gemm_mfma_bert_large_pmc_traffic.md,
 # each counter scaled by what it reads for the library's copy kernel of known size (1.990 / 1.000).
 # Counters cannot be read from inside this process, so the figure is carried here per workload.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"bert_large": 64959596}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"bert_large": 64959032}
 
 
 def stage_flops(cfg, M):
@@ -130,6 +130,7 @@ def main():
     ap.add_argument("--workload", default="bert_large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pipeline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -202,28 +203,29 @@ def main():
 
     # the early-backward iteration again as ONE HIP graph (captured once on a stream of its own, then
     # replayed): what is left when the host issues one launch per iteration instead of one per kernel
-    with torch.cuda.stream(torch.cuda.Stream()):
-        rg = B.StageRunner(c_config(cfg, K), theta)
-        gio = make_io(rg)
-        gp = gio[-1]
-        B.stage_zero_grads(rg.h)
-        B.stage_run_schedule(rg.h, M, K, B.ORDER_EARLY_BACKWARD, gp[0], gp[1], gp[2], gp[3], gp[4])
-        B.stage_sync(rg.h)
-        B.stage_graph_capture(rg.h, M, K, B.ORDER_EARLY_BACKWARD, gp[0], gp[1], gp[2], gp[3], gp[4], zero_grads_first=True)
-        for _ in range(args.warmup):
-            B.stage_graph_launch(rg.h)
-        B.stage_sync(rg.h)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            B.stage_graph_launch(rg.h)
-        B.stage_sync(rg.h)
-        torch.cuda.synchronize()
-        results["graph"] = (time.perf_counter() - t0) / args.steps
-        del gio
-        rg.close()
-        del rg
-    torch.cuda.empty_cache()
+    if not args.no_graph:
+        with torch.cuda.stream(torch.cuda.Stream()):
+            rg = B.StageRunner(c_config(cfg, K), theta)
+            gio = make_io(rg)
+            gp = gio[-1]
+            B.stage_zero_grads(rg.h)
+            B.stage_run_schedule(rg.h, M, K, B.ORDER_EARLY_BACKWARD, gp[0], gp[1], gp[2], gp[3], gp[4])
+            B.stage_sync(rg.h)
+            B.stage_graph_capture(rg.h, M, K, B.ORDER_EARLY_BACKWARD, gp[0], gp[1], gp[2], gp[3], gp[4], zero_grads_first=True)
+            for _ in range(args.warmup):
+                B.stage_graph_launch(rg.h)
+            B.stage_sync(rg.h)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                B.stage_graph_launch(rg.h)
+            B.stage_sync(rg.h)
+            torch.cuda.synchronize()
+            results["graph"] = (time.perf_counter() - t0) / args.steps
+            del gio
+            rg.close()
+            del rg
+        torch.cuda.empty_cache()
 
     # per-kernel-class times: the same steps again with HIP events around every launch
     r, step = runner
@@ -284,8 +286,9 @@ def main():
                       "throughput_vs_stored": sec / results["early_backward_recompute"],
                       "memory_vs_stored": peak_bytes["early_backward_recompute"] / peak_bytes["early_backward"],
                       "memory_vs_gpipe_order": peak_bytes["early_backward_recompute"] / peak_bytes["gpipe"]},
-        "hip_graph_replay": {"samples_per_s": M * cfg.micro_batch / results["graph"], "ms_per_step": results["graph"] * 1e3,
-                             "note": "one hipGraphLaunch per iteration (one backward lane inside the graph)"},
+        "hip_graph_replay": None if args.no_graph else
+        {"samples_per_s": M * cfg.micro_batch / results["graph"], "ms_per_step": results["graph"] * 1e3,
+         "note": "one hipGraphLaunch per iteration (one backward lane inside the graph)"},
         "apply_adam": {"ms": apply_ms, "params": int(r.sizes.n_params), "bytes": int(apply_bytes),
                        "GB/s": apply_bytes / (apply_ms * 1e-3) / 1e9, "hbm_peak_frac": apply_bytes / (apply_ms * 1e-3) / 8e12},
         "kernel_classes": classes,
