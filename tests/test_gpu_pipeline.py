@@ -158,3 +158,45 @@ def test_pipeline_create_error_paths():
         B.pipeline_partition_stream_create(3, 3)
     with pytest.raises(B.StageError):
         B.pipeline_warmup_depths(0, 4)
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", TOL_F32), ("bf16", TOL_BF16)])
+def test_whole_model_as_three_stages_follows_the_oracle(dtype, tol):
+    """Embedding block on the first stage, MLM head on the last: token ids in, losses out, every gradient of the
+    unsplit model against the float64 oracle of the unsplit model."""
+    import torch
+    if dtype == "f32":
+        full = I.StageConfig(3, 64, 4, 128, 16, 2, 4, 3, "f32", has_embedding=True, has_mlm_head=True, vocab=200,
+                             max_pos=16, ln_eps=1e-5)
+    else:
+        full = I.StageConfig(3, 128, 2, 256, 64, 2, 4, 3, "bf16", has_embedding=True, has_mlm_head=True, vocab=520,
+                             max_pos=64)
+    S, M = 3, 4
+    theta, mbs = make_inputs(full, SEED, M)
+    kw = dict(vocab=full.vocab, max_pos=full.max_pos, ln_eps=full.ln_eps)
+    parts = [I.StageConfig(1, full.hidden, full.n_heads, full.ffn, full.seq, full.micro_batch, M, 3, dtype,
+                           has_embedding=(i == 0), has_mlm_head=(i == S - 1), **kw) for i in range(S)]
+    sizes = [I.n_params(p) for p in parts]
+    assert sum(sizes) == theta.size
+    cuts = np.cumsum([0] + sizes)
+    K = B.pipeline_warmup_depths(S, M, B.POLICY_A)
+    pr = B.PipelineRunner([c_config(parts[i], K[i]) for i in range(S)], [theta[cuts[i]:cuts[i + 1]] for i in range(S)], M,
+                          parts=0)
+    try:
+        T = full.tokens
+        r0 = pr.runners[0]
+        xs = [r0.to_dev(mb["ids"].reshape(T).astype(np.int32)) for mb in mbs]
+        auxs = [r0.to_dev(mb["targets"].reshape(T).astype(np.int32)) for mb in mbs]
+        ys = [torch.zeros(1, dtype=torch.float32, device="cuda") for _ in range(M)]
+        for r in pr.runners:
+            B.stage_zero_grads(r.h)
+        torch.cuda.synchronize()
+        pr.run(M, K, B.ORDER_EARLY_BACKWARD, xs, None, auxs, ys, None)
+        torch.cuda.synchronize()
+        got = dict(ys=[to_np(y) for y in ys], dxs=None,
+                   grads=np.concatenate([r.grads.cpu().numpy() for r in pr.runners]))
+        assert [B.stage_stats(r.h).peak_live_slots for r in pr.runners] == K
+    finally:
+        pr.close()
+    st, ref = run_oracle(full, theta, mbs, M, 3)
+    compare(full, st, ref, got, tol, M)
