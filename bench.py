@@ -77,13 +77,12 @@ def pipeline_study(cfg, seed, S=4, layers_per_stage=3, M=16):
 
     from paper_2007_01045_amd import binding as B
     from paper_2007_01045_amd import inputs as I
-    from tests.stage_util import c_config
 
     part = I.StageConfig(layers_per_stage, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, M, S, cfg.dtype,
                          ln_eps=cfg.ln_eps, name="pipeline_part")
     T, H = part.tokens, part.hidden
     K = B.pipeline_warmup_depths(S, M, B.POLICY_A)
-    pr = B.PipelineRunner([c_config(part, M, flags=B.FLAG_ONE_STREAM) for _ in range(S)],
+    pr = B.PipelineRunner([B.config_for(part, M, flags=B.FLAG_ONE_STREAM) for _ in range(S)],
                           [I.make_params(part, seed + i) for i in range(S)], M, parts=S)
     try:
         r0 = pr.runners[0]
@@ -143,7 +142,6 @@ def main():
 
     from paper_2007_01045_amd import binding as B
     from paper_2007_01045_amd import inputs as I
-    from tests.stage_util import c_config
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -173,7 +171,7 @@ def main():
     for order_name, order, slots, flags in (("gpipe", B.ORDER_GPIPE, M, 0),
                                             ("early_backward_recompute", B.ORDER_EARLY_BACKWARD, K, B.FLAG_RECOMPUTE),
                                             ("early_backward", B.ORDER_EARLY_BACKWARD, K, 0)):
-        r = B.StageRunner(c_config(cfg, slots, flags=flags), theta)
+        r = B.StageRunner(B.config_for(cfg, slots, flags=flags), theta)
         xs, dys, ys, dxs, auxs, (px, pdy, py, pdx, paux) = make_io(r)
 
         def step():
@@ -205,7 +203,7 @@ def main():
     # replayed): what is left when the host issues one launch per iteration instead of one per kernel
     if not args.no_graph:
         with torch.cuda.stream(torch.cuda.Stream()):
-            rg = B.StageRunner(c_config(cfg, K), theta)
+            rg = B.StageRunner(B.config_for(cfg, K), theta)
             gio = make_io(rg)
             gp = gio[-1]
             B.stage_zero_grads(rg.h)

@@ -146,6 +146,18 @@ def make_config(n_layers, hidden, n_heads, ffn, seq, micro_batch, max_slots, dty
 
 
 # ---- thin wrappers, one per C entry point ---------------------------------
+def config_for(cfg, max_slots, loss_scale=1.0, flags=0) -> stage_config:
+    """The C configuration of a stage described by inputs.StageConfig (the seeded-input module's shape record);
+    a stage with the MLM head gets room for the 15% of positions the input recipe predicts."""
+    import math
+    tokens = cfg.micro_batch * cfg.seq
+    return make_config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, max_slots,
+                       DTYPE_BF16 if cfg.dtype == "bf16" else DTYPE_F32, cfg.has_embedding, cfg.has_mlm_head,
+                       cfg.vocab if (cfg.has_embedding or cfg.has_mlm_head) else 0,
+                       cfg.max_pos if cfg.has_embedding else 0, flags, cfg.ln_eps, loss_scale,
+                       math.ceil(0.15 * tokens) if cfg.has_mlm_head else 0)
+
+
 def stage_query_sizes(cfg: stage_config) -> stage_sizes:
     out = stage_sizes()
     _check(load().stage_query_sizes(C.byref(cfg), C.byref(out)))

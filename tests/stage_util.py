@@ -17,12 +17,7 @@ def to_np(t):
 
 
 def c_config(cfg: I.StageConfig, max_slots, loss_scale=1.0, flags=0):
-    import math
-    return B.make_config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, max_slots,
-                         B.DTYPE_BF16 if cfg.dtype == "bf16" else B.DTYPE_F32, cfg.has_embedding,
-                         cfg.has_mlm_head, cfg.vocab if (cfg.has_embedding or cfg.has_mlm_head) else 0,
-                         cfg.max_pos if cfg.has_embedding else 0, flags, cfg.ln_eps, loss_scale,
-                         math.ceil(0.15 * cfg.tokens) if cfg.has_mlm_head else 0)
+    return B.config_for(cfg, max_slots, loss_scale, flags)
 
 
 def oracle_stage(cfg, theta, loss_scale=1.0):
