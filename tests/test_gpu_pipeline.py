@@ -200,3 +200,23 @@ def test_whole_model_as_three_stages_follows_the_oracle(dtype, tol):
         pr.close()
     st, ref = run_oracle(full, theta, mbs, M, 3)
     compare(full, st, ref, got, tol, M)
+
+
+@pytest.mark.parametrize("S,M", [(1, 3), (2, 1), (3, 2)])
+def test_degenerate_pipelines(S, M):
+    # one stage (no boundary at all), one micro-batch, fewer micro-batches than stages: K_i is capped at M
+    cfg = I.StageConfig(6, 64, 4, 128, 16, 2, M, 3, "f32", ln_eps=1e-5)
+    theta, mbs = make_inputs(cfg, SEED, M)
+    K = B.pipeline_warmup_depths(S, M, B.POLICY_A)
+    assert K == PO.warmup_depths(S, M, "A") and max(K) <= M
+    one = run_gpu(cfg, theta, mbs, M, max(K), B.ORDER_EARLY_BACKWARD)
+    pipe = Pipe(cfg, S, K, theta, M, parts=0)
+    try:
+        got = pipe.run(M, K, B.ORDER_EARLY_BACKWARD, mbs)
+    finally:
+        pipe.close()
+    assert got["peak"] == K
+    assert np.array_equal(got["grads"], one["grads"])
+    for m in range(M):
+        assert np.array_equal(got["ys"][m], one["ys"][m]) and np.array_equal(got["dxs"][m], one["dxs"][m])
+    check_timeline(got["timeline"], S, M, PO.stage_lists(S, M, K))
