@@ -220,3 +220,21 @@ def test_degenerate_pipelines(S, M):
     for m in range(M):
         assert np.array_equal(got["ys"][m], one["ys"][m]) and np.array_equal(got["dxs"][m], one["dxs"][m])
     check_timeline(got["timeline"], S, M, PO.stage_lists(S, M, K))
+
+
+def test_recomputing_stages_in_a_pipeline_give_the_same_bits():
+    cfg = I.StageConfig(4, 64, 4, 128, 16, 2, 5, 2, "f32", ln_eps=1e-5)
+    S, M = 2, 5
+    theta, mbs = make_inputs(cfg, SEED, M)
+    K = B.pipeline_warmup_depths(S, M, B.POLICY_A)
+    out = []
+    for flags in (0, B.FLAG_RECOMPUTE, B.FLAG_RECOMPUTE | B.FLAG_ONE_STREAM):
+        pipe = Pipe(cfg, S, K, theta, M, parts=0, flags=flags)
+        try:
+            out.append(pipe.run(M, K, B.ORDER_EARLY_BACKWARD, mbs))
+        finally:
+            pipe.close()
+    for o in out[1:]:
+        assert o["peak"] == K and np.array_equal(o["grads"], out[0]["grads"])
+        for m in range(M):
+            assert np.array_equal(o["dxs"][m], out[0]["dxs"][m]) and np.array_equal(o["ys"][m], out[0]["ys"][m])

@@ -354,3 +354,56 @@ def test_one_stream_flag_changes_no_bit():
     assert np.array_equal(a["grads"], b["grads"])
     for m in range(5):
         assert np.array_equal(a["ys"][m], b["ys"][m]) and np.array_equal(a["dxs"][m], b["dxs"][m])
+
+
+@pytest.mark.parametrize("kind", ["recompute", "first_stage", "last_stage", "gpipe_order"])
+def test_graph_replays_of_the_other_stage_kinds(kind):
+    """A captured iteration of a re-computing stage, a first stage (token ids in), a last stage (losses out) and of
+    the GPipe order: two replays with an eager iteration between them, each equal to the eager result bit for bit."""
+    import torch
+    flags, order = 0, B.ORDER_EARLY_BACKWARD
+    if kind == "first_stage":
+        cfg = I.StageConfig(2, 128, 2, 256, 64, 2, 4, 2, "bf16", has_embedding=True, vocab=500, max_pos=64)
+    elif kind == "last_stage":
+        cfg = I.StageConfig(2, 128, 2, 256, 64, 2, 4, 2, "bf16", has_mlm_head=True, vocab=520)
+    else:
+        cfg = I.StageConfig(3, 256, 4, 512, 128, 2, 4, 2, "bf16")
+        flags = B.FLAG_RECOMPUTE if kind == "recompute" else 0
+        order = B.ORDER_GPIPE if kind == "gpipe_order" else order
+    M, K = 4, 2
+    slots = M if order == B.ORDER_GPIPE else K
+    theta, mbs = make_inputs(cfg, SEED, M)
+    eager = run_gpu(cfg, theta, mbs, M, K, order, flags=flags)
+    T, H = cfg.tokens, cfg.hidden
+    emb, head = cfg.has_embedding, cfg.has_mlm_head
+    with torch.cuda.stream(torch.cuda.Stream()):
+        r = B.StageRunner(c_config(cfg, slots, flags=flags), theta)
+        try:
+            xs = [r.to_dev(mb["ids"].reshape(T).astype(np.int32)) if emb else r.to_dev(mb["x"].reshape(T, H)) for mb in mbs]
+            dys = None if head else [r.to_dev(mb["dy"].reshape(T, H)) for mb in mbs]
+            auxs = [r.to_dev(mb["targets"].reshape(T).astype(np.int32)) for mb in mbs] if head else None
+            ys = [torch.zeros(1, dtype=torch.float32, device="cuda") if head else r.empty_act() for _ in range(M)]
+            dxs = None if emb else [r.empty_act() for _ in range(M)]
+            ptr = lambda ts: None if ts is None else [t.data_ptr() for t in ts]
+            args = (r.h, M, K, order, ptr(xs), ptr(dys), ptr(ys), ptr(dxs), ptr(auxs))
+            B.stage_zero_grads(r.h)
+            B.stage_run_schedule(*args)
+            B.stage_sync(r.h)
+            B.stage_graph_capture(*args, zero_grads_first=True)
+            for rep in range(2):
+                for t in ys + (dxs or []):
+                    t.zero_()
+                r.grads.fill_(3.0)
+                B.stage_graph_launch(r.h)
+                B.stage_sync(r.h)
+                torch.cuda.synchronize()
+                assert np.array_equal(r.grads.cpu().numpy(), eager["grads"]), rep
+                for m in range(M):
+                    assert np.array_equal(to_np(ys[m]), eager["ys"][m])
+                    assert emb or np.array_equal(to_np(dxs[m]), eager["dxs"][m])
+                B.stage_zero_grads(r.h)
+                B.stage_run_schedule(*args)
+                B.stage_sync(r.h)
+                assert np.array_equal(r.grads.cpu().numpy(), eager["grads"])
+        finally:
+            r.close()
