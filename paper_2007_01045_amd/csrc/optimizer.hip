@@ -29,10 +29,11 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ G, float*
     ((float4*)w32)[i] = wv;
     ((float4*)m)[i] = mv;
     ((float4*)v)[i] = vv;
-    w[4 * i] = from_f32<T>(wv.x);
-    w[4 * i + 1] = from_f32<T>(wv.y);
-    w[4 * i + 2] = from_f32<T>(wv.z);
-    w[4 * i + 3] = from_f32<T>(wv.w);
+    // the four weights of the stage's dtype leave in one store (w is 16-byte aligned like the fp32 vectors)
+    typedef T T4 __attribute__((ext_vector_type(4)));
+    T4 o;
+    o[0] = from_f32<T>(wv.x); o[1] = from_f32<T>(wv.y); o[2] = from_f32<T>(wv.z); o[3] = from_f32<T>(wv.w);
+    *(T4*)(w + 4 * i) = o;
     if (zero_grads) ((float4*)G)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
   // the last n % 4 parameters
