@@ -216,3 +216,25 @@ def test_colsum(dtype):
     B.dapple_colsum(dtype, dX.data_ptr(), rows, cols, ld, partial.data_ptr(), out.data_ptr())
     torch.cuda.synchronize()
     assert rel_l2(to_np(out) - 2.0, X[:, :cols].sum(0)) < 1e-5
+
+
+@pytest.mark.parametrize("seed", [5, 6])
+def test_gemm_random_shapes(seed):
+    """Random M, N, K (ragged against every tile size), layouts, epilogues, batches, K segments and tile
+    choices, bf16 and fp32: whichever kernel takes the problem must agree with the float64 product."""
+    import random
+    rng = random.Random(seed)
+    epis = [0, B.EPI_BIAS, B.EPI_BIAS | B.EPI_ADD, B.EPI_MUL, B.EPI_ADD, B.EPI_BIAS | B.EPI_GELU, B.EPI_ACC32]
+    for case in range(30):
+        dtype = rng.choice([B.DTYPE_BF16, B.DTYPE_BF16, B.DTYPE_F32])
+        M = rng.choice([rng.randint(1, 64), rng.randint(65, 700), 8 * rng.randint(1, 80)])
+        N = rng.choice([4 * rng.randint(1, 150), 8 * rng.randint(1, 70), rng.randint(1, 300)])
+        nseg = rng.choice([1, 1, 2, 3])
+        K = nseg * 8 * rng.randint(1, 40)
+        akS, bkS = rng.random() < 0.5, rng.random() < 0.5
+        epi = rng.choice(epis)
+        batch = rng.choice([1, 1, 2, 3])
+        tile = rng.randint(0, 7)
+        print(f"case {case}: dtype={dtype} M={M} N={N} K={K} akS={akS} bkS={bkS} epi={epi} batch={batch} nseg={nseg} "
+              f"tile={tile}", flush=True)
+        gemm_case(dtype, M, N, K, akS, bkS, epi, batch=batch, nseg=nseg, tile=tile)
