@@ -238,3 +238,15 @@ def test_gemm_random_shapes(seed):
         print(f"case {case}: dtype={dtype} M={M} N={N} K={K} akS={akS} bkS={bkS} epi={epi} batch={batch} nseg={nseg} "
               f"tile={tile}", flush=True)
         gemm_case(dtype, M, N, K, akS, bkS, epi, batch=batch, nseg=nseg, tile=tile)
+
+
+def test_attention_random_shapes():
+    import random
+    rng = random.Random(9)
+    for case in range(16):
+        dtype = rng.choice([B.DTYPE_BF16, B.DTYPE_F32])
+        d = rng.choice([64, 64, 32, 16, 8])
+        A, b = rng.randint(1, 4), rng.randint(1, 3)
+        s = rng.choice([64, 128, 192, 320, 8, 24, 100])
+        print(f"case {case}: dtype={dtype} b={b} s={s} A={A} d={d}", flush=True)
+        attention_case(dtype, b, s, A, d)
