@@ -73,7 +73,7 @@ struct Layout {
   int NP = 0, VP = 0;
   size_t sh_rows = 0, sh_tgt = 0, sh_r = 0, sh_gl = 0, sh_glp = 0, sh_st = 0, sh_t = 0, sh_dz = 0;
   size_t wh_logits = 0, wh_rowloss = 0, wh_dt = 0, wh_dgl = 0, wh_dh = 0, wh_dr = 0, wh_dyfull = 0, wh_part = 0,
-         wh_info = 0;
+         wh_part_cz = 0, wh_part_ch = 0, wh_info = 0;
   size_t wh_logits2 = 0, wh_rowloss2 = 0, wh_info2 = 0;  // second set: the forward re-run inside a backward task
   size_t we_dx0 = 0, we_de = 0, we_part = 0;
   // fp32 copies of LayerNorm outputs for the residual adds (bf16 stages); set 1: the forward re-run
@@ -195,7 +195,9 @@ void build_layout(const stage_config& c, Layout& L) {
     L.wh_logits = wtake(NP * VP * 4); L.wh_rowloss = wtake(NP * 4); L.wh_dt = wtake(NP * H * E);
     L.wh_dgl = wtake(NP * H * E); L.wh_dh = wtake(NP * H * E); L.wh_dr = wtake(NP * H * E); L.wh_dyfull = wtake(U);
     size_t lp = ((NP + 7) / 8) * 3 * H * 4, cp = ((NP + 63) / 64) * VP * 4;
-    L.wh_part = wtake(lp > cp ? lp : cp); L.wh_info = wtake(16);
+    // three partial-sum buffers: the LayerNorm backward writes its own on the backward stream while the side
+    // stream is still reducing a column sum
+    L.wh_part = wtake(lp); L.wh_part_cz = wtake(cp); L.wh_part_ch = wtake(((NP + 63) / 64) * H * 4); L.wh_info = wtake(16);
     if (L.recompute) { L.wh_logits2 = wtake(NP * VP * 4); L.wh_rowloss2 = wtake(NP * 4); L.wh_info2 = wtake(16); }
   }
   if (c.has_embedding) {
@@ -475,13 +477,18 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     float *hst = (float*)(sl + L.sh_st), *part = (float*)ws(L.wh_part);
     char *dtb = ws(L.wh_dt), *dgl = ws(L.wh_dgl), *dh = ws(L.wh_dh), *dr = ws(L.wh_dr), *dyfull = ws(L.wh_dyfull);
     int nblk = 0;
+    // The head's accumulator updates go to the side stream like the layers' (fork events of the pseudo-layer
+    // n_layers), in the order dE_out, db_out, LayerNorm gain and shift, dWt, dbt.
+    const int HL = cfg.n_layers;
+    float *part_cz = (float*)ws(L.wh_part_cz), *part_ch = (float*)ws(L.wh_part_ch);
+    TRY(fork(HL, 0));
     {  // dE_out += dz^T t
       GemmArgs ga{};
       ga.A = dz; ga.lda = VP; ga.a_kstrided = 1; ga.B = t; ga.ldb = H; ga.b_kstrided = 1;
       ga.C = gr(L.hEout); ga.ldc = H; ga.M = V; ga.N = H; ga.K = NP; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_HEAD, ga));
+      TRY(gemm(KC_HEAD, ga, nullptr, true));
     }
-    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_colsum(dt, dz, NP, V, VP, part, gr(L.hbout), 1, 0, 0, q); }));
+    TRY(run_on(side, KC_HEAD, 0, [&](hipStream_t q) { return launch_colsum(dt, dz, NP, V, VP, part_cz, gr(L.hbout), 1, 0, 0, q); }));
     {  // dt = dz E_out
       GemmArgs ga{};
       ga.A = dz; ga.lda = VP; ga.B = w(L.hEout); ga.ldb = H; ga.b_kstrided = 1; ga.k_valid = V;
@@ -489,15 +496,18 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       TRY(gemm(KC_HEAD, ga));
     }
     TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dtb, gl, false, hst, w(L.hG), dgl, part, &nblk, NP, H, q); }));
-    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.hG), gr(L.hB), nullptr, q); }));
+    TRY(fork(HL, 1));
+    TRY(run_on(side, KC_HEAD, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.hG), gr(L.hB), nullptr, q); }));
     TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_mul(dt, dgl, glp, dh, (long)NP * H, q); }));
+    TRY(fork(HL, 0));   // event 0 again: the side stream's first wait on it is already enqueued
     {  // dWt += r^T dh
       GemmArgs ga{};
       ga.A = r; ga.lda = H; ga.a_kstrided = 1; ga.B = dh; ga.ldb = H; ga.b_kstrided = 1;
       ga.C = gr(L.hWt); ga.ldc = H; ga.M = H; ga.N = H; ga.K = NP; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_HEAD, ga));
+      TRY(gemm(KC_HEAD, ga, nullptr, true));
     }
-    TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_colsum(dt, dh, NP, H, H, part, gr(L.hbt), 1, 0, 0, q); }));
+    TRY(run_on(side, KC_HEAD, 0, [&](hipStream_t q) { return launch_colsum(dt, dh, NP, H, H, part_ch, gr(L.hbt), 1, 0, 0, q); }));
+    TRY(side_done(HL));
     {  // dr = dh Wt^T
       GemmArgs ga{};
       ga.A = dh; ga.lda = H; ga.B = w(L.hWt); ga.ldb = H; ga.C = dr; ga.ldc = H; ga.M = NP; ga.N = H; ga.K = H;
@@ -637,16 +647,22 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     TRY(run(KC_EMBED, 0, [&](hipStream_t q) {
       return launch_ln_bwd(dt, dyin, esum, false, (const float*)(sl + L.slot_embst), w(L.embG), de, part, &nblk, T, H, q);
     }));
-    TRY(run(KC_EMBED, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.embG), gr(L.embB), nullptr, q); }));
-    TRY(run(KC_EMBED, 0, [&](hipStream_t q) {
+    // the three accumulations (LayerNorm gain and shift, the two tables) join the side stream's queue like every
+    // other accumulator update, so that backward tasks may run on two lanes: fork event 3 of layer 0 is free
+    // again (its side work was enqueued above), and the task's closing join below waits for this too
+    TRY(fork(0, 3));
+    TRY(run_on(side2, KC_EMBED, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.embG), gr(L.embB), nullptr, q); }));
+    TRY(run_on(side2, KC_EMBED, 0, [&](hipStream_t q) {
       return launch_embed_bwd(dt, (const int32_t*)(sl + L.slot_ids), de, gr(L.embEw), gr(L.embEp), cfg.micro_batch,
                               cfg.seq, H, cfg.vocab, q);
     }));
+    TRY(side_done(0));
   }
   // The task ends when both streams are done: whatever follows on the caller's stream (the next
   // forward reusing this slot, a gradient read-out) is ordered after the accumulator updates.
   TRY(join(0));
   if (cfg.n_layers > 1) TRY(join(1));
+  if (cfg.has_mlm_head) TRY(join(cfg.n_layers));
   return STAGE_OK;
 }
 
@@ -778,7 +794,7 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
     }
     // the forward lane and the second backward lane are made by the first stage_run_schedule that uses lanes:
     // a stage driven task by task (stage_fwd / stage_bwd, the pipeline of several stages) holds no idle queues
-    h->ev.resize((size_t)cfg->n_layers * 6);
+    h->ev.resize((size_t)(cfg->n_layers + 1) * 6);   // one more set for the head's side work
     h->ev_f.resize(cfg->max_slots);
     h->ev_b.resize(cfg->max_slots);
     std::vector<hipEvent_t*> all;
@@ -946,13 +962,12 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
   // Early-backward order, plain stages: consecutive backward tasks alternate between the caller's
   // stream and a second backward stream (each with its own copy of the workspace), so the head of
   // B_{j+1} overlaps the tail of B_j.  Their accumulator updates still happen in list order: all of
-  // them are issued, in host order, on the one side stream.  (A first or last stage also
-  // accumulates on its backward stream -- embedding tables, head -- and keeps one backward lane.)
+  // them are issued, in host order, on the one side stream (the embedding block's and the head's too).
   // A capture keeps to one backward lane: the HIP runtime that ships with PyTorch 2.10 (ROCm 7.0) recurses
   // without end in hipStreamEndCapture once two streams other than the capture's origin have waited for each
   // other's events (side lane <-> second backward lane); the origin may wait for and be waited for by anyone.
   static const int bwd_lanes_env = envi("DAPPLE_BWD_LANES");
-  const bool two = lanes && !strict && h->L.ws_copies == 2 && !h->cfg.has_embedding && !h->cfg.has_mlm_head &&
+  const bool two = lanes && !strict && h->L.ws_copies == 2 &&
                    !h->no_side && bwd_lanes_env != 1 && !h->capturing;
   int n_bwd = 0;
   bool used_b2 = false;
