@@ -967,7 +967,9 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
   // without end in hipStreamEndCapture once two streams other than the capture's origin have waited for each
   // other's events (side lane <-> second backward lane); the origin may wait for and be waited for by anyone.
   static const int bwd_lanes_env = envi("DAPPLE_BWD_LANES");
-  const bool two = lanes && !strict && h->L.ws_copies == 2 &&
+  // (The GPipe order alternates its backward tasks the same way once every forward is done; an explicit list
+  // keeps one backward lane.)
+  const bool two = lanes && order != STAGE_ORDER_EXPLICIT && h->L.ws_copies == 2 &&
                    !h->no_side && bwd_lanes_env != 1 && !h->capturing;
   int n_bwd = 0;
   bool used_b2 = false;
