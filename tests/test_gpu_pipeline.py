@@ -5,7 +5,9 @@ import numpy as np
 import pytest
 
 from oracle import pipeline_oracle as PO
-from stage_util import *  # noqa: F401,F403
+from paper_2007_01045_amd import binding as B
+from paper_2007_01045_amd import inputs as I
+from tests.stage_util import c_config, compare, make_inputs, run_gpu, run_oracle, to_np
 
 pytestmark = pytest.mark.gpu
 

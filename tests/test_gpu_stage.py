@@ -22,8 +22,11 @@ def check_config(cfg, M, K, tol, loss_scale=1.0):
     st, ref = run_oracle(cfg, theta, mbs, M, K, loss_scale=loss_scale)
     eb = run_gpu(cfg, theta, mbs, M, K, B.ORDER_EARLY_BACKWARD, loss_scale=loss_scale)
     gp = run_gpu(cfg, theta, mbs, M, K, B.ORDER_GPIPE, loss_scale=loss_scale)
-    worst = compare(cfg, st, ref, eb, tol, M)
-    compare(cfg, st, ref, gp, tol, M)
+    rep = {}
+    worst = compare(cfg, st, ref, eb, tol, M, mbs, rep)
+    compare(cfg, st, ref, gp, tol, M, mbs)
+    print(f"[{cfg.name or 'stage'} M={M} K={K}] worst rel-L2 {worst[1]:.3e} ({worst[0]}), worst element "
+          f"{rep['worst_elem'][1]:.3e} rms ({rep['worst_elem'][0]}), worst table rows {rep['rows']}", flush=True)
     # the two orders run the same kernels on the same data and add the micro-batch
     # gradients in the same sequence: results must agree bit for bit
     assert np.array_equal(eb["grads"], gp["grads"])
@@ -149,6 +152,38 @@ def test_bert48_quarter_full_shapes_reduced_M():
     cfg = I.CONFIGS["bert48_quarter"]
     worst = check_config(cfg, 5, 4, TOL_BF16)
     print("bert48_quarter worst:", worst)
+
+
+def _full_config(name, loss_scale=1.0):
+    """A named configuration at its stated M and K against the oracle, both orders, plus a run without lanes
+    (one stream) that must give the same bits: the steady state of the schedule (M - K slot reuses, alternating
+    backward lanes, the side lane's accumulation order) at full shapes."""
+    cfg = I.CONFIGS[name]
+    print(f"{name}: oracle for M={cfg.M}, K={cfg.K} ...", flush=True)
+    worst = check_config(cfg, cfg.M, cfg.K, TOL_BF16, loss_scale=loss_scale)
+    theta, mbs = make_inputs(cfg, SEED, cfg.M)
+    eb = run_gpu(cfg, theta, mbs, cfg.M, cfg.K, B.ORDER_EARLY_BACKWARD, loss_scale=loss_scale)
+    one = run_gpu(cfg, theta, mbs, cfg.M, cfg.K, B.ORDER_EARLY_BACKWARD, loss_scale=loss_scale, flags=B.FLAG_ONE_STREAM)
+    assert np.array_equal(eb["grads"], one["grads"])
+    for m in range(cfg.M):
+        assert np.array_equal(eb["ys"][m], one["ys"][m])
+        if eb["dxs"] is not None:
+            assert np.array_equal(eb["dxs"][m], one["dxs"][m])
+    assert one["stats"]["peak_live"] == cfg.K and one["stats"]["peak_bytes"] == cfg.K * one["stats"]["slot_bytes"]
+    return worst
+
+
+def test_bert48_quarter_at_stated_M_and_K():
+    _full_config("bert48_quarter")
+
+
+def test_first_stage_at_stated_M_and_K():
+    _full_config("first_stage")
+
+
+def test_last_stage_at_stated_M_and_K():
+    cfg = I.CONFIGS["last_stage"]
+    _full_config("last_stage", loss_scale=1.0 / (cfg.M * 154))
 
 
 def test_bert_large_shaped_stage_full_size():
