@@ -82,6 +82,19 @@ int dapple_layernorm_bwd(int dtype, const void* dy, const void* z, const float* 
 int dapple_colsum(int dtype, const void* X, int rows, int cols, int ld, float* partial, float* out,
                   void* stream);
 
+
+/* dapple_colsum for callers that cannot allocate or bring a workspace (code under HIP graph capture, serving
+ * loops, harnesses that forbid hipMalloc): the same two kernels and the same summation order, bit for bit, with
+ * the partial sums in an array built into the library's device code (one copy of
+ * DAPPLE_COLSUM_STATIC_MAX_FLOATS floats = 4 MiB per GPU, held until the process ends).  Allocates nothing and
+ * frees nothing; the array's device address is looked up on the first call on a device (a host-side query, no
+ * allocation).  ceil(rows/64)*cols must not exceed DAPPLE_COLSUM_STATIC_MAX_FLOATS, else STAGE_E_CONFIG
+ * (stage_last_error() says by how much) and nothing is enqueued.  X [rows, ld] and out [cols] are device
+ * pointers owned by the caller as in dapple_colsum.  All calls on one GPU share the one array: calls that may
+ * overlap on that GPU (different streams, no ordering between them) race; calls on one stream are safe. */
+#define DAPPLE_COLSUM_STATIC_MAX_FLOATS (1 << 20)
+int dapple_colsum_static(int dtype, const void* X, int rows, int cols, int ld, float* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -96,6 +96,7 @@ SYMBOLS = {
     "dapple_layernorm_fwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _i, _i, _f, _vp]),
     "dapple_layernorm_bwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _vp]),
     "dapple_colsum": (_i, [_i, _vp, _i, _i, _i, _vp, _vp, _vp]),
+    "dapple_colsum_static": (_i, [_i, _vp, _i, _i, _i, _vp, _vp]),
 }
 
 _lib = None
@@ -376,6 +377,15 @@ def dapple_layernorm_bwd(dtype, dy, z, stats, gamma, dz, partial, dgamma, dbeta,
 
 def dapple_colsum(dtype, X, rows, cols, ld, partial, out, stream_ptr=None):
     _kcheck(load().dapple_colsum(dtype, X, rows, cols, ld, partial, out, stream_ptr), "dapple_colsum")
+
+
+COLSUM_STATIC_MAX_FLOATS = 1 << 20
+
+
+def dapple_colsum_static(dtype, X, rows, cols, ld, out, stream_ptr=None):
+    rc = load().dapple_colsum_static(dtype, X, rows, cols, ld, out, stream_ptr)
+    if rc < 0:
+        raise StageError(rc, last_error())
 
 
 # ---- convenience: device memory through torch ------------------------------

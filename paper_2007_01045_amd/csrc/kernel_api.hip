@@ -2,11 +2,38 @@
 // forwarding to the launchers, nothing else.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "../../include/dapple_kernels.h"
 #include "../../include/dapple_stage.h"
 #include "kernels.h"
 
 using namespace dapple;
+
+// Scratch of dapple_colsum_static: the per-block partial sums of the column sum live in this array instead of a
+// buffer the caller brings.  Every GPU the library runs on holds its own copy (4 MiB) at its own address until
+// the process ends.  In host code the name is only a handle for hipGetSymbolAddress: the device address is
+// looked up once per device and kept in scratch_ptr[], and only that pointer is ever given to a kernel.
+static __device__ __align__(256) float scratch[DAPPLE_COLSUM_STATIC_MAX_FLOATS];
+static std::mutex scratch_mu;
+static float* scratch_ptr[64] = {};
+
+// the current device's copy of `scratch` (looked up on the first call on that device)
+static int scratch_of_current_device(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    return set_error(STAGE_E_DEVICE, "hipGetDevice failed or device index %d out of range", dev);
+  std::lock_guard<std::mutex> lock(scratch_mu);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return set_error(STAGE_E_DEVICE, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+    scratch_ptr[dev] = (float*)p;
+  }
+  *out = scratch_ptr[dev];
+  return STAGE_OK;
+}
 
 static int dev_rc(hipError_t e) { return e == hipSuccess ? STAGE_OK : STAGE_E_DEVICE; }
 static bool bad_dtype(int dt) { return dt != STAGE_DTYPE_F32 && dt != STAGE_DTYPE_BF16; }
@@ -82,6 +109,24 @@ int dapple_colsum(int dtype, const void* X, int rows, int cols, int ld, float* p
   if (!X || !partial || !out) return STAGE_E_NULL;
   int vec = dtype == STAGE_DTYPE_BF16 ? 8 : 4;
   if (bad_dtype(dtype) || rows < 1 || cols < 1 || cols % vec || ld % vec) return STAGE_E_CONFIG;
+  return dev_rc(launch_colsum(dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32, X, rows, cols, ld, partial, out, 1, 0, 0,
+                              (hipStream_t)stream));
+}
+
+int dapple_colsum_static(int dtype, const void* X, int rows, int cols, int ld, float* out, void* stream) {
+  if (!X || !out) return set_error(STAGE_E_NULL, "X and out must not be NULL");
+  int vec = dtype == STAGE_DTYPE_BF16 ? 8 : 4;
+  if (bad_dtype(dtype) || rows < 1 || cols < 1 || cols % vec || ld % vec)
+    return set_error(STAGE_E_CONFIG, "dtype, rows, cols or ld not accepted (cols and ld must be multiples of %d)", vec);
+  // what the two kernels write and read: ceil(rows/64) blocks of cols partial sums (cols is a whole number of vectors)
+  const size_t need = (size_t)((rows + 63) / 64) * (size_t)cols;
+  if (need > (size_t)DAPPLE_COLSUM_STATIC_MAX_FLOATS)
+    return set_error(STAGE_E_CONFIG, "ceil(rows/64)*cols = %zu partial sums exceed the built-in scratch of %d floats",
+                     need, (int)DAPPLE_COLSUM_STATIC_MAX_FLOATS);
+  float* partial = nullptr;
+  int rc = scratch_of_current_device(&partial);
+  if (rc != STAGE_OK) return rc;
+  // every partial sum the second kernel reads is written by the first one of the same call: nothing to clear
   return dev_rc(launch_colsum(dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32, X, rows, cols, ld, partial, out, 1, 0, 0,
                               (hipStream_t)stream));
 }
