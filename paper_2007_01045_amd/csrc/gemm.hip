@@ -76,16 +76,17 @@ __global__ void gemm_plain_kernel(GemmArgs g) {
 }
 
 // ------------------------------------------------------------------ MFMA kernel
-constexpr int BK = 64;
 constexpr unsigned BUF_RSRC_FLAGS = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
 
 typedef __attribute__((__vector_size__(4 * sizeof(int)))) int int4v;
 
-// One operand's [R x 64] tile of a k-step in LDS, filled by buffer loads that
+// One operand's [R x BK] tile of a k-step in LDS (BK = 64 or 32), filled by buffer loads that
 // write straight into LDS (16 bytes per lane, 1 KiB contiguous per wave
 // instruction; out-of-range offsets read as zero, so ragged edges need no
 // branches) and read back as MFMA fragments.
-//   k-contiguous operand: LDS [row][8 chunks of 16 B], chunk' = chunk ^ ((row >> 1) & 7)
+//   k-contiguous operand: LDS [row][BK/8 chunks of 16 B], chunk' = chunk ^ rswz(row)
+//                         (BK = 64: (row >> 1) & 7; BK = 32: (row >> 2) & 3 -- in both cases the 16 rows a
+//                         group of 16 lanes reads spread over all 16 sixteen-byte slots of a 256-byte bank row)
 //   k-strided operand:    LDS [k][R/8 chunks],         chunk' = chunk ^ kswz(k)
 // LDS has 64 banks of 4 bytes: a 128-bit read is served 16 lanes at a time and a
 // 64-bit (transpose) read 32 lanes at a time, each group needing 256 distinct
@@ -110,13 +111,18 @@ __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
-template <int R, bool KS, int NW>
+template <int R, bool KS, int NW, int BK>
 struct OperandTile {
-  static constexpr int NI = R * 8 / (64 * NW);  // load instructions per wave per k-step
+  static_assert(BK == 64 || BK == 32, "k-tiles of 64 or 32");
+  static constexpr int CH = BK / 8;                   // 16-byte chunks per row of a k-contiguous tile
+  static constexpr int NI = R * CH / (64 * NW);       // load instructions per wave per k-tile
   static constexpr int LDS_ELEMS = R * BK;
   static constexpr int LDS_BYTES = LDS_ELEMS * 2;
-  static_assert(R * 8 % (64 * NW) == 0, "tile rows must split evenly over the waves");
-  int voff[NI];  // per-lane byte offset of each load inside the k-step's slab
+  static_assert(R * CH % (64 * NW) == 0, "tile rows must split evenly over the waves");
+  int voff[NI];  // per-lane byte offset of each load inside the k-tile's slab
+
+  // chunk swizzle of row `row` of a k-contiguous tile
+  static __device__ __forceinline__ int rswz(int row) { return BK == 64 ? (row >> 1) & 7 : (row >> 2) & 3; }
 
   // chunk swizzle of k row k of a k-strided tile: rows of 256 B or more rotate by 64 B per
   // row (4 rows cover 256 B); rows of 128 B alternate halves every second row
@@ -135,7 +141,7 @@ struct OperandTile {
     for (int j = 0; j < NI; ++j) {
       int pos = (wave * NI + j) * 64 + lane;
       if (!KS) {
-        int row = pos >> 3, kc = (pos & 7) ^ ((row >> 1) & 7);
+        int row = pos / CH, kc = (pos % CH) ^ rswz(row);
         voff[j] = ((r0 + row) * ld + kc * 8) * 2;
       } else {
         int krow = pos / (R / 8), c = (pos % (R / 8)) ^ kswz(krow);
@@ -151,8 +157,10 @@ struct OperandTile {
   // purpose: through the compiler builtin every LDS read that follows waits for ALL outstanding
   // loads (the compiler cannot tell the ring slots apart), which would undo the multi-stage
   // pipeline.  The kernel keeps its own count instead (s_waitcnt vmcnt(n) before the barrier).
-  template <int LDS_OFF>
-  __device__ __forceinline__ void load(int4v rs, int wave_off) const {
+  static constexpr int NGROUPS = NI / GROUP;
+  // one group (G0 = its first chunk) of the k-tile's requests
+  template <int LDS_OFF, int G0>
+  __device__ __forceinline__ void load_group(int4v rs, int wave_off) const {
     // uniform already; this only tells the compiler so (no instruction when it is in SGPRs)
     rs[0] = __builtin_amdgcn_readfirstlane(rs[0]);
     rs[1] = __builtin_amdgcn_readfirstlane(rs[1]);
@@ -165,47 +173,49 @@ struct OperandTile {
     // assembles the 4-register tuple right before the block: s_nop 4), and a scalar write of M0
     // needs 1 before the LDS-direct load that uses it (s_nop 0).  One block per group, so that
     // nothing the compiler emits can come between the M0 write and its loads.
-#pragma unroll
-    for (int g0 = 0; g0 < NI; g0 += GROUP) {
-      if constexpr (GROUP == 4) {
-        asm volatile(
-            "s_nop 4\n\ts_add_u32 m0, %0, %1\n\ts_nop 0\n\t"
-            "buffer_load_dwordx4 %2, %6, 0 offen lds\n\t"
-            "buffer_load_dwordx4 %3, %6, 0 offen offset:1024 lds\n\t"
-            "buffer_load_dwordx4 %4, %6, 0 offen offset:2048 lds\n\t"
-            "buffer_load_dwordx4 %5, %6, 0 offen offset:3072 lds"
-            :
-            : "s"(wave_off), "i"(LDS_OFF + g0 * 1024), "v"(voff[g0]), "v"(voff[g0 + 1]), "v"(voff[g0 + 2]),
-              "v"(voff[g0 + 3]), "s"(rs)
-            : "memory", "m0", "scc");
-      } else {
-        asm volatile(
-            "s_nop 4\n\ts_add_u32 m0, %0, %1\n\ts_nop 0\n\t"
-            "buffer_load_dwordx4 %2, %4, 0 offen lds\n\t"
-            "buffer_load_dwordx4 %3, %4, 0 offen offset:1024 lds"
-            :
-            : "s"(wave_off), "i"(LDS_OFF + g0 * 1024), "v"(voff[g0]), "v"(voff[g0 + 1]), "s"(rs)
-            : "memory", "m0", "scc");
-      }
+    if constexpr (GROUP == 4) {
+      asm volatile(
+          "s_nop 4\n\ts_add_u32 m0, %0, %1\n\ts_nop 0\n\t"
+          "buffer_load_dwordx4 %2, %6, 0 offen lds\n\t"
+          "buffer_load_dwordx4 %3, %6, 0 offen offset:1024 lds\n\t"
+          "buffer_load_dwordx4 %4, %6, 0 offen offset:2048 lds\n\t"
+          "buffer_load_dwordx4 %5, %6, 0 offen offset:3072 lds"
+          :
+          : "s"(wave_off), "i"(LDS_OFF + G0 * 1024), "v"(voff[G0]), "v"(voff[G0 + 1]), "v"(voff[G0 + 2]),
+            "v"(voff[G0 + 3]), "s"(rs)
+          : "memory", "m0", "scc");
+    } else {
+      asm volatile(
+          "s_nop 4\n\ts_add_u32 m0, %0, %1\n\ts_nop 0\n\t"
+          "buffer_load_dwordx4 %2, %4, 0 offen lds\n\t"
+          "buffer_load_dwordx4 %3, %4, 0 offen offset:1024 lds"
+          :
+          : "s"(wave_off), "i"(LDS_OFF + G0 * 1024), "v"(voff[G0]), "v"(voff[G0 + 1]), "s"(rs)
+          : "memory", "m0", "scc");
     }
+  }
+  template <int LDS_OFF>
+  __device__ __forceinline__ void load(int4v rs, int wave_off) const {
+    static_for<NGROUPS>([&](auto G) { load_group<LDS_OFF, decltype(G)::value * GROUP>(rs, wave_off); });
   }
 };
 
 // LDS byte addresses of a lane's MFMA fragments, relative to the operand's tile:
 // rows w0 + 32*blk + (lane & 31), k = kk*16 + 8*(lane>>5) + 0..7.  Everything that depends
 // on blk, kk or the ring slot beyond these few registers is an instruction immediate.
-template <int R, bool KS, int NB>
+template <int R, bool KS, int NB, int BK>
 struct FragAddr {
-  unsigned a[KS ? NB : 4];
+  static constexpr int KSTEPS = BK / 16;
+  unsigned a[KS ? NB : KSTEPS];
   __device__ __forceinline__ void init(int w0, int lane) {
     if (!KS) {
-      int r = lane & 31, sw = (r >> 1) & 7;  // w0 is a multiple of 32: the swizzle sees lane bits only
+      int r = lane & 31, sw = OperandTile<R, KS, 4, BK>::rswz(r);  // w0 is a multiple of 32: the swizzle sees lane bits only
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) a[kk] = (unsigned)((w0 + r) * (BK * 2) + (((kk * 2 + (lane >> 5)) ^ sw) << 4));
+      for (int kk = 0; kk < KSTEPS; ++kk) a[kk] = (unsigned)((w0 + r) * (BK * 2) + (((kk * 2 + (lane >> 5)) ^ sw) << 4));
     } else {
       int i16 = lane & 15, g16 = (lane >> 4) & 1, h = lane >> 5;
       int krow = 8 * h + (i16 >> 2);
-      int sw = OperandTile<R, KS, 4>::kswz(i16 >> 2);  // depends on krow & 3 only
+      int sw = OperandTile<R, KS, 4, BK>::kswz(i16 >> 2);  // depends on krow & 3 only
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
         int col = w0 + 32 * b + 16 * g16 + 4 * (i16 & 3);
@@ -225,12 +235,12 @@ struct FragAddr {
   }
 };
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS>
+template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS, int BK>
 struct GemmTile {
   static constexpr int NW = WGM * WGN, NT = 64 * NW;
   static constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
-  typedef OperandTile<BM, AKS, NW> TA;
-  typedef OperandTile<BN, BKS, NW> TB;
+  typedef OperandTile<BM, AKS, NW, BK> TA;
+  typedef OperandTile<BN, BKS, NW, BK> TB;
   static constexpr int STAGE_ELEMS = TA::LDS_ELEMS + TB::LDS_ELEMS;
   static constexpr int EPI_LD = WN + 4;  // fp32 staging row
   static constexpr size_t MAIN_BYTES = NS * (size_t)STAGE_ELEMS * sizeof(bf16);
@@ -239,9 +249,9 @@ struct GemmTile {
   static constexpr size_t LDS_BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
 };
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS>
+template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS, int BK>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
-  typedef GemmTile<BM, BN, WGM, WGN, NS, AKS, BKS> CFG;
+  typedef GemmTile<BM, BN, WGM, WGN, NS, AKS, BKS, BK> CFG;
   typedef typename CFG::TA TA;
   typedef typename CFG::TB TB;
   constexpr int MI = CFG::MI, NI = CFG::NI;
@@ -282,9 +292,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   const int m0 = tm * BM, n0 = tn * BN;
   const int z = blockIdx.z;
 
-  const bf16* Ab = g.Az[0] ? (const bf16*)g.Az[z] : (const bf16*)g.A + z * g.sA;
-  const bf16* Bb = g.Bz[0] ? (const bf16*)g.Bz[z] : (const bf16*)g.B + z * g.sB;
-  void* const Cb = g.Cz[0] ? g.Cz[z] : g.C;
+  // (the per-instance pointers are picked with constant indices: a variable index would move the whole
+  // argument struct to scratch memory, and with it every value the k-loop derives from it out of scalar registers)
+  auto pick = [&](auto& arr) { return z == 0 ? arr[0] : (z == 1 ? arr[1] : (z == 2 ? arr[2] : arr[3])); };
+  const bf16* Ab = g.Az[0] ? (const bf16*)pick(g.Az) : (const bf16*)g.A + z * g.sA;
+  const bf16* Bb = g.Bz[0] ? (const bf16*)pick(g.Bz) : (const bf16*)g.B + z * g.sB;
+  void* const Cb = g.Cz[0] ? pick(g.Cz) : g.C;
   const int nk = g.K / BK;
   const int tiles_per_seg = g.kseg_len / BK;
   // bytes of one segment of each operand that may be read (beyond: zero)
@@ -297,8 +310,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   TB tb;
   ta.init(g.lda, m0, wave, lane);
   tb.init(g.ldb, n0, wave, lane);
-  FragAddr<BM, AKS, MI> fa;
-  FragAddr<BN, BKS, NI> fb;
+  FragAddr<BM, AKS, MI, BK> fa;
+  FragAddr<BN, BKS, NI, BK> fb;
   fa.init(wm0, lane);
   fb.init(wn0, lane);
   const int wave_off_a = wave * TA::NI * 1024, wave_off_b = wave * TB::NI * 1024;
@@ -364,36 +377,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   struct Frags {
     bf16x8 a[MI], b[NI];
   };
-  auto load_frags = [&](Frags& f, auto S, auto KK) {
-    constexpr int off = decltype(S)::value * CFG::STAGE_ELEMS * 2, kk = decltype(KK)::value;
-    static_for<MI>([&](auto I) { f.a[decltype(I)::value] = fa.template get<off, decltype(I)::value, kk>(smem); });
-    static_for<NI>([&](auto J) { f.b[decltype(J)::value] = fb.template get<off + TA::LDS_BYTES, decltype(J)::value, kk>(smem); });
-  };
-  auto mfma_step = [&](const Frags& f) {
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-      for (int j = 0; j < NI; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
-  };
-  auto compute = [&](auto S) {
-    Frags f0, f1;
-    load_frags(f0, S, std::integral_constant<int, 0>{});
-    load_frags(f1, S, std::integral_constant<int, 1>{});
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_step(f0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(f0, S, std::integral_constant<int, 2>{});
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_step(f1);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(f1, S, std::integral_constant<int, 3>{});
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_step(f0);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_step(f1);
-  };
-  static_assert(BK == 64, "compute() spells out the four k-steps of a tile");
+  constexpr int KSTEPS = BK / 16;
+  static_assert(KSTEPS % 2 == 0, "the two fragment sets alternate over an even number of k-steps");
 
   // The loop runs whole turns of the ring: K is padded to a multiple of NS k-tiles with
   // tiles that read nothing (zeros in LDS add nothing), and every iteration requests a tile,
@@ -407,16 +392,68 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   // nothing delivers its zeros within a few clocks)
   constexpr int WAIT_TILE = (INFLIGHT & 15) | ((INFLIGHT >> 4) << 14) | 0x0070;  // expcnt: no wait
   static_for<NS - 1>([&](auto T) { issue_loads(T); });
+  // The k-steps are rotated by one against the tiles: the MFMAs of a tile's LAST k-step are issued after the
+  // barrier that opens the next tile (their fragments were read before it).  Everything else a tile needs --
+  // the LDS reads of the next k-step's fragments, the requests for the tile NS - 1 ahead, the cursor arithmetic
+  // -- is cut in pieces and placed BETWEEN the MFMAs of a k-step in a fixed order (nothing may be moved across
+  // the fences): a wave issues an instruction every few clocks while an MFMA holds the matrix pipe for 32, so
+  // in the shadow of each MFMA there is room for a few other instructions and the pipe never waits for them.
+  // The very first rotated step multiplies zeros.
+  Frags f0, f1;
+  static_for<MI>([&](auto I) { f1.a[decltype(I)::value] = bf16x8{}; });
+  static_for<NI>([&](auto J) { f1.b[decltype(J)::value] = bf16x8{}; });
+  constexpr int GA = TA::NGROUPS, GB = TB::NGROUPS, EXTRA = GA + GB + 1;  // request groups of A, of B, the cursor step
+  constexpr int NFRAG = MI + NI, NM = MI * NI;
+  // step J of tile S: the MFMAs of `use`; between them the reads of `fill` (the fragments of k-step J of tile S,
+  // in the order the next step's MFMAs need them: a0, b0 .. b_NI-1, a1 ..) and this step's share of the requests
+  // for the tile that goes to ring slot SN
+  auto step = [&](const Frags& use, Frags& fill, auto S, auto SN, auto J) {
+    constexpr int off = decltype(S)::value * CFG::STAGE_ELEMS * 2, offn = decltype(SN)::value * CFG::STAGE_ELEMS * 2;
+    constexpr int j = decltype(J)::value;
+    constexpr int e0 = j * EXTRA / KSTEPS, e1 = (j + 1) * EXTRA / KSTEPS, P = NFRAG + (e1 - e0);
+    static_for<NM>([&](auto Q) {
+      constexpr int q = decltype(Q)::value, mi = q / NI, ni = q % NI;
+      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(use.b[ni], use.a[mi], acc[mi][ni], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      constexpr int p0 = q * P / NM, p1 = (q + 1) * P / NM;
+      static_for<p1 - p0>([&](auto D) {
+        constexpr int p = p0 + decltype(D)::value;
+        if constexpr (p == 0) {
+          fill.a[0] = fa.template get<off, 0, j>(smem);
+        } else if constexpr (p <= NI) {
+          fill.b[p - 1] = fb.template get<off + TA::LDS_BYTES, p - 1, j>(smem);
+        } else if constexpr (p < NFRAG) {
+          fill.a[p - NI] = fa.template get<off, p - NI, j>(smem);
+        } else {
+          constexpr int e = e0 + (p - NFRAG);
+          if constexpr (e < GA) ta.template load_group<offn, e * TA::GROUP>(ars, wave_off_a);
+          else if constexpr (e < GA + GB) tb.template load_group<offn + TA::LDS_BYTES, (e - GA) * TB::GROUP>(brs, wave_off_b);
+          else advance();
+        }
+      });
+      if constexpr (p1 > p0) __builtin_amdgcn_sched_barrier(0);
+    });
+  };
   const int turns = (nk + NS - 1) / NS;
   for (int t = 0; t < turns; ++t) {
     static_for<NS>([&](auto S) {
+      typedef std::integral_constant<int, (decltype(S)::value + NS - 1) % NS> SN;
       __builtin_amdgcn_sched_barrier(0);  // no LDS read of the previous tile may sink below the barrier
       __builtin_amdgcn_s_waitcnt(WAIT_TILE);
       __builtin_amdgcn_s_barrier();  // every wave's part of this tile is in LDS; the previous tile's slot is free
-      issue_loads(std::integral_constant<int, (decltype(S)::value + NS - 1) % NS>{});
-      compute(S);
+      asm volatile("" ::: "memory");  // ... and no LDS read of this tile may be hoisted above it
+      static_for<KSTEPS / 2>([&](auto H) {
+        constexpr int kk = 2 * decltype(H)::value;
+        step(f1, f0, S, SN{}, std::integral_constant<int, kk>{});      // MFMAs of k-step kk - 1 (the previous tile's last when kk == 0)
+        step(f0, f1, S, SN{}, std::integral_constant<int, kk + 1>{});
+      });
     });
   }
+  // the last k-step of the last tile
+  static_for<NM>([&](auto Q) {
+    constexpr int q = decltype(Q)::value, mi = q / NI, ni = q % NI;
+    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[ni], f1.a[mi], acc[mi][ni], 0, 0, 0);
+  });
   __builtin_amdgcn_s_waitcnt(0x0F70);  // the tail requests (they read nothing) must be done before LDS is reused
   __syncthreads();  // every wave has read its last fragments: LDS can be reused
 
@@ -551,26 +588,29 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
 }
 
 // explicit instantiations (every tile shape x operand layout the launcher can pick)
-#define DAPPLE_GEMM_INST(BM, BN, WGM, WGN, NS)                                                        \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, false>(GemmArgs, int, int); \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, true>(GemmArgs, int, int);  \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, false>(GemmArgs, int, int);  \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, true>(GemmArgs, int, int);
-DAPPLE_GEMM_INST(256, 256, 2, 2, 2)
-DAPPLE_GEMM_INST(256, 128, 2, 2, 3)
-DAPPLE_GEMM_INST(128, 128, 2, 2, 2)
-DAPPLE_GEMM_INST(128, 128, 2, 2, 4)
-DAPPLE_GEMM_INST(128, 64, 2, 2, 2)
-DAPPLE_GEMM_INST(128, 64, 2, 2, 3)
-DAPPLE_GEMM_INST(128, 64, 2, 2, 4)
+#define DAPPLE_GEMM_INST(BM, BN, WGM, WGN, NS, BK)                                                        \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, false, BK>(GemmArgs, int, int); \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, true, BK>(GemmArgs, int, int);  \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, false, BK>(GemmArgs, int, int);  \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, true, BK>(GemmArgs, int, int);
+DAPPLE_GEMM_INST(256, 256, 2, 2, 2, 64)
+DAPPLE_GEMM_INST(256, 128, 2, 2, 3, 64)
+DAPPLE_GEMM_INST(128, 128, 2, 2, 2, 64)
+DAPPLE_GEMM_INST(128, 128, 2, 2, 4, 64)
+DAPPLE_GEMM_INST(128, 64, 2, 2, 2, 64)
+DAPPLE_GEMM_INST(128, 64, 2, 2, 3, 64)
+DAPPLE_GEMM_INST(128, 64, 2, 2, 4, 64)
+DAPPLE_GEMM_INST(256, 256, 2, 2, 4, 32)
+DAPPLE_GEMM_INST(256, 256, 2, 2, 5, 32)
+DAPPLE_GEMM_INST(256, 128, 2, 2, 6, 32)
 #undef DAPPLE_GEMM_INST
 
 // ------------------------------------------------------------------ host side
-template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS>
+template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS, int BK>
 static hipError_t launch_mfma(const GemmArgs& g, hipStream_t st) {
-  typedef GemmTile<BM, BN, WGM, WGN, NS, AKS, BKS> CFG;
+  typedef GemmTile<BM, BN, WGM, WGN, NS, AKS, BKS, BK> CFG;
   static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, NS, AKS, BKS>;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, NS, AKS, BKS, BK>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)CFG::LDS_BYTES);
@@ -583,20 +623,21 @@ static hipError_t launch_mfma(const GemmArgs& g, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS>
+template <int BM, int BN, int WGM, int WGN, int NS, int BK = 64>
 static hipError_t launch_mfma_layout(const GemmArgs& g, hipStream_t st) {
   if (g.a_kstrided) {
-    return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, NS, true, true>(g, st)
-                        : launch_mfma<BM, BN, WGM, WGN, NS, true, false>(g, st);
+    return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, NS, true, true, BK>(g, st)
+                        : launch_mfma<BM, BN, WGM, WGN, NS, true, false, BK>(g, st);
   }
-  return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, NS, false, true>(g, st)
-                      : launch_mfma<BM, BN, WGM, WGN, NS, false, false>(g, st);
+  return g.b_kstrided ? launch_mfma<BM, BN, WGM, WGN, NS, false, true, BK>(g, st)
+                      : launch_mfma<BM, BN, WGM, WGN, NS, false, false, BK>(g, st);
 }
 
 static bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
   if (dt != DT_BF16) return false;
+  constexpr int BK = 64;  // every tile configuration takes K and the K segments in multiples of 64
   if (g.K < BK || g.K % BK || g.kseg_len % BK || g.K % g.kseg_len) return false;
   if (g.lda % 8 || g.ldb % 8 || g.ldc % 4 || g.N % 4) return false;
   if (g.sA % 8 || g.sB % 8 || g.sC % 4 || g.sBias % 4 || g.segA % 8 || g.segB % 8) return false;
@@ -635,6 +676,9 @@ hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st) {
       case 5: return launch_mfma_layout<128, 64, 2, 2, 2>(g, st);
       case 6: return launch_mfma_layout<128, 64, 2, 2, 3>(g, st);
       case 7: return launch_mfma_layout<128, 64, 2, 2, 4>(g, st);
+      case 8: return launch_mfma_layout<256, 256, 2, 2, 4, 32>(g, st);
+      case 9: return launch_mfma_layout<256, 256, 2, 2, 5, 32>(g, st);
+      case 10: return launch_mfma_layout<256, 128, 2, 2, 6, 32>(g, st);
       default: break;
     }
     // tile choice (measured on the BERT-Large-shaped stage with its three streams running):
