@@ -24,8 +24,10 @@ enum {
   DAPPLE_EPI_ADD = 2,   /* t += aux[m,n]  (residual branch) */
   DAPPLE_EPI_MUL = 4,   /* t *= aux[m,n]  (GELU' gate in the FFN backward) */
   DAPPLE_EPI_GELU = 8,  /* C = GELU(t), C2 = GELU'(t) */
-  DAPPLE_EPI_ACC32 = 16 /* C is fp32 and C += t  (weight-gradient accumulation over
-                           micro-batches, section V-B-3 of the DAPPLE paper) */
+  DAPPLE_EPI_ACC32 = 16, /* C is fp32 and C += t  (weight-gradient accumulation over
+                            micro-batches, section V-B-3 of the DAPPLE paper) */
+  DAPPLE_EPI_BSUM = 128  /* bsum[n] += sum_k B(n,k): the bias gradient (column sums of the output gradient)
+                            in the launch of the weight gradient; both operands k-strided, batch 1 */
 };
 
 /* C[m,n] = epilogue(sum_k A(m,k) B(n,k)).  A k-contiguous operand is X(r,k) =
@@ -42,6 +44,7 @@ typedef struct {
   void* C2;
   const void* bias;
   const void* aux;
+  float* bsum;    /* DAPPLE_EPI_BSUM: fp32 [N], accumulated into */
   int32_t M, N, K;
   int32_t lda, ldb, ldc, ldaux;
   int32_t a_kstrided, b_kstrided;
@@ -51,9 +54,9 @@ typedef struct {
   int64_t sA, sB, sC, sBias;
   int32_t k_valid;
   int32_t epi;
-  int32_t tile;   /* 0 = automatic; 1..7 = a specific tile shape and LDS ring depth of the MFMA kernel
-                   * (1: 256x256/2, 2: 256x128/3, 3: 128x128/2, 4: 128x128/4, 5: 128x64/2, 6: 128x64/3,
-                   * 7: 128x64/4), for tests and tuning */
+  int32_t tile;   /* 0 = automatic; else one configuration of the MFMA kernel, for tests and timing:
+                   * 1: 256x256 tile, four-stage ring of 32-wide k-tiles; 2: 256x128, three stages of 64;
+                   * 3: 128x128, two stages of 64; 4: 128x64, three stages of 64 */
 } dapple_gemm_desc;
 
 /* Returns 1 if the bf16 MFMA kernel takes this problem, 0 if the plain kernel does. */

@@ -29,15 +29,19 @@
  *     sub-allocates the arena handed to stage_init (gradient accumulators,
  *     max_slots activation slots, workspace).
  *   - all device work is ordered in the HIP stream given to stage_init; no call
- *     synchronises the stream except stage_sync.  (A backward task also uses a second,
- *     library-owned stream for the gradient-accumulator kernels, and stage_run_schedule
- *     a third one for its forward tasks; both are forked from and joined back into the
- *     caller's stream inside the call, so the caller's stream order still covers
- *     everything.)  Buffers passed to a call must stay valid until the
- *     stream has passed that call.
+ *     synchronises the stream except stage_sync.  (The library owns up to three more
+ *     streams: one for the gradient-accumulator kernels of every backward task, and,
+ *     inside stage_run_schedule, one for the forward tasks and one for every second
+ *     backward task.  All are forked from and joined back into the caller's stream
+ *     inside the call, so the caller's stream order still covers everything.)
+ *     Buffers passed to a call must stay valid until the stream has passed that call.
  *   - every call returns 0 on success or a negative STAGE_E_* code; nothing throws
  *     or aborts.  stage_last_error() gives a message for the last failure of the
- *     calling thread.  A failed call enqueues nothing and changes no state.
+ *     calling thread.  A call that fails with any code but STAGE_E_DEVICE has enqueued
+ *     nothing and changed no state (arguments, orders and slot use are checked on the
+ *     host first).  STAGE_E_DEVICE means a HIP call failed part-way: work may already
+ *     be enqueued and micro-batches may be left resident; the only calls defined on
+ *     such a handle are stage_sync and stage_destroy.
  *   - element type: dtype 0 = fp32 everywhere; dtype 1 = bf16 storage for
  *     weights, activations and boundary tensors with fp32 accumulation inside
  *     kernels and fp32 gradient accumulators.
@@ -154,9 +158,14 @@ int stage_schedule_ops(int M, int K, int order, int32_t* ops_out, int capacity);
  * before anything is enqueued.
  * The early-backward order is executed as the dependence graph that defines it
  * (the control edges B_m -> F_{m+K} of section V-C plus F_m -> B_m, forwards in
- * list order, backwards in list order): forward tasks go to the library's forward
- * stream and overlap the backward tasks on the caller's stream.  The other two
- * orders are executed strictly as listed.  Results do not depend on the overlap. */
+ * list order): forward tasks go to the library's forward stream, backward tasks
+ * alternate between the caller's stream and a second backward stream (each with
+ * its own workspace), and every gradient-accumulator update of every backward task
+ * goes to the one side stream in list order, which fixes the order of every sum.
+ * The GPipe order alternates its backward tasks the same way but starts none before
+ * the last forward listed before it has finished; an explicit list keeps one backward
+ * stream and the same rule.  Results do not depend on the overlap: they are the same
+ * bits as with STAGE_FLAG_ONE_STREAM. */
 int stage_run_schedule(stage_handle h, int M, int K, int order,
                        const void* const* xs, const void* const* dys,
                        void* const* ys, void* const* dxs, const void* const* auxs,
@@ -215,6 +224,17 @@ int stage_reset_stats(stage_handle h);
  * stage_profile_class_name(i), NULL past the end. */
 int stage_profile_enable(stage_handle h, int on);
 int stage_profile_read(stage_handle h, int n, uint64_t* launches, double* ms, double* flops);
+/* The launches timed since stage_profile_enable / the last stage_profile_read, one record each, in
+ * the order they were enqueued (call it before stage_profile_read, which clears them): class,
+ * stream (0 = caller's, 1 = side, 2 = forward, 3 = second backward), milliseconds, algorithmic
+ * flops, and for matrix products M, N, K and the number of products in the launch (0 otherwise).
+ * Synchronises the stage's streams.  Returns the number of records written (at most capacity). */
+typedef struct {
+  int32_t cls, lane;
+  int32_t M, N, K, batch;
+  double ms, flops;
+} stage_launch_record;
+int stage_profile_launches(stage_handle h, stage_launch_record* out, int capacity);
 const char* stage_profile_class_name(int i);
 
 int stage_sync(stage_handle h);

@@ -22,7 +22,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 FLAG_DRY_RUN = 1
 FLAG_RECOMPUTE = 2
 FLAG_ONE_STREAM = 4
-EPI_BIAS, EPI_ADD, EPI_MUL, EPI_GELU, EPI_ACC32 = 1, 2, 4, 8, 16
+EPI_BIAS, EPI_ADD, EPI_MUL, EPI_GELU, EPI_ACC32, EPI_BSUM = 1, 2, 4, 8, 16, 128
 
 
 class stage_config(C.Structure):
@@ -45,7 +45,7 @@ class stage_stats_t(C.Structure):
 
 class dapple_gemm_desc(C.Structure):
     _fields_ = [("A", C.c_void_p), ("B", C.c_void_p), ("C", C.c_void_p), ("C2", C.c_void_p),
-                ("bias", C.c_void_p), ("aux", C.c_void_p),
+                ("bias", C.c_void_p), ("aux", C.c_void_p), ("bsum", C.c_void_p),
                 ("M", C.c_int32), ("N", C.c_int32), ("K", C.c_int32),
                 ("lda", C.c_int32), ("ldb", C.c_int32), ("ldc", C.c_int32), ("ldaux", C.c_int32),
                 ("a_kstrided", C.c_int32), ("b_kstrided", C.c_int32), ("kseg_len", C.c_int32),
@@ -75,6 +75,7 @@ SYMBOLS = {
     "stage_reset_stats": (_i, [_vp]),
     "stage_profile_enable": (_i, [_vp, _i]),
     "stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_uint64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "stage_profile_launches": (_i, [_vp, _vp, _i]),
     "stage_profile_class_name": (C.c_char_p, [_i]),
     "stage_sync": (_i, [_vp]),
     "stage_destroy": (_i, [_vp]),
@@ -334,6 +335,20 @@ def stage_profile_read(h):
     launches, ms, flops = (C.c_uint64 * n)(), (C.c_double * n)(), (C.c_double * n)()
     _check(load().stage_profile_read(h, n, launches, ms, flops))
     return {names[i]: dict(launches=launches[i], ms=ms[i], flops=flops[i]) for i in range(n)}
+
+
+class stage_launch_record(C.Structure):
+    _fields_ = [("cls", C.c_int32), ("lane", C.c_int32), ("M", C.c_int32), ("N", C.c_int32), ("K", C.c_int32),
+                ("batch", C.c_int32), ("ms", C.c_double), ("flops", C.c_double)]
+
+
+def stage_profile_launches(h, capacity=1 << 16):
+    """The launches timed since profiling was enabled (call before stage_profile_read): a list of dicts."""
+    buf = (stage_launch_record * capacity)()
+    n = _check(load().stage_profile_launches(h, buf, capacity))
+    lib = load()
+    return [dict(cls=(lib.stage_profile_class_name(r.cls) or b"?").decode(), lane=r.lane, M=r.M, N=r.N, K=r.K,
+                 batch=r.batch, ms=r.ms, flops=r.flops) for r in buf[:n]]
 
 
 def stage_sync(h):

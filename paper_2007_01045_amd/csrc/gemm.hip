@@ -4,8 +4,8 @@
 //
 //  * gemm_mfma_kernel: bf16 operands, fp32 accumulation on the gfx950 matrix
 //    cores (v_mfma_f32_32x32x16_bf16).  256 threads = 4 waves in a 2x2 grid over a
-//    BM x BN tile, BK = 64 per step, LDS double-buffered and filled by buffer loads
-//    that write straight into LDS.  k-contiguous operands sit in LDS as [row][64]
+//    BM x BN tile, k-tiles of 64 or 32, an LDS ring of 2 to 4 k-tiles filled by buffer
+//    loads that write straight into LDS.  k-contiguous operands sit in LDS as [row][k]
 //    and are read with 128-bit loads; k-strided operands sit as [k][rows] and are
 //    read with the LDS transpose read, so no transposed copy of an activation or a
 //    weight is ever made in HBM (both layouts XOR-swizzled against bank conflicts).  The MFMA is issued with the B fragment as its
@@ -14,7 +14,6 @@
 //  * gemm_plain_kernel: one thread per output element, fp32 accumulation in k
 //    order; used for fp32 stages (the tiny configuration) and for shapes the MFMA
 //    kernel does not take.
-#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -60,7 +59,7 @@ __global__ void gemm_plain_kernel(GemmArgs g) {
     g.C = g.Cz[z];
     g.sC = 0;
   }
-  float acc = 0.f;
+  float acc = 0.f, bsum = 0.f;
   int nseg = g.K / g.kseg_len;
   for (int s = 0; s < nseg; ++s) {
     const T* As = A + s * g.segA;
@@ -70,7 +69,12 @@ __global__ void gemm_plain_kernel(GemmArgs g) {
       float a = row < g.m_valid ? to_f32(g.a_kstrided ? As[(long)k * g.lda + row] : As[(long)row * g.lda + k]) : 0.f;
       float b = col < g.n_valid ? to_f32(g.b_kstrided ? Bs[(long)k * g.ldb + col] : Bs[(long)col * g.ldb + k]) : 0.f;
       acc = fmaf(a, b, acc);
+      bsum += b;
     }
+  }
+  if ((g.epi & EPI_BSUM) && row == 0) {
+    float* bs = z == 0 ? g.bsum_z[0] : (z == 1 ? g.bsum_z[1] : (z == 2 ? g.bsum_z[2] : g.bsum_z[3]));
+    if (bs) bs[col] += bsum;
   }
   epilogue_store<T>(g, z * g.sC, z * g.sBias, row, col, acc);
 }
@@ -249,7 +253,8 @@ struct GemmTile {
   static constexpr size_t LDS_BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
 };
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS, int BK>
+// CS: the variant that can also sum B over k (EPI_BSUM)
+template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS, int BK, bool CS>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
   typedef GemmTile<BM, BN, WGM, WGN, NS, AKS, BKS, BK> CFG;
   typedef typename CFG::TA TA;
@@ -407,13 +412,30 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   // step J of tile S: the MFMAs of `use`; between them the reads of `fill` (the fragments of k-step J of tile S,
   // in the order the next step's MFMAs need them: a0, b0 .. b_NI-1, a1 ..) and this step's share of the requests
   // for the tile that goes to ring slot SN
-  auto step = [&](const Frags& use, Frags& fill, auto S, auto SN, auto J) {
+  // EPI_BSUM: bsum[n] += sum_k B(n,k) for this tile's columns, by the workgroups of the first tile row (tm == 0)
+  // and there by the waves that hold the tile's first rows: one more MFMA per column block and k-step with an
+  // A fragment of ones -- every row of its result is the column sum, exact products, fp32 adds in k order.
+  // The matrix pipe has the room (the products wait for the global -> LDS path), and the column sums of the
+  // output gradient need no pass of their own over it.
+  f32x16 csum[CS ? NI : 1];
+#pragma unroll
+  for (int j = 0; j < (CS ? NI : 1); ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) csum[j][v] = 0.f;
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (bf16)1.0f;
+  float* const bsum_ptr = CS ? pick(g.bsum_z) : nullptr;
+  const bool do_cs = CS && (g.epi & EPI_BSUM) && tm == 0 && wm0 == 0 && bsum_ptr != nullptr;
+  auto step = [&](const Frags& use, Frags& fill, auto S, auto SN, auto J, auto WCS) {
     constexpr int off = decltype(S)::value * CFG::STAGE_ELEMS * 2, offn = decltype(SN)::value * CFG::STAGE_ELEMS * 2;
     constexpr int j = decltype(J)::value;
     constexpr int e0 = j * EXTRA / KSTEPS, e1 = (j + 1) * EXTRA / KSTEPS, P = NFRAG + (e1 - e0);
     static_for<NM>([&](auto Q) {
       constexpr int q = decltype(Q)::value, mi = q / NI, ni = q % NI;
       acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(use.b[ni], use.a[mi], acc[mi][ni], 0, 0, 0);
+      if constexpr (decltype(WCS)::value && mi == 0)
+        csum[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(use.b[ni], ones, csum[ni], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       constexpr int p0 = q * P / NM, p1 = (q + 1) * P / NM;
       static_for<p1 - p0>([&](auto D) {
@@ -435,25 +457,36 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
     });
   };
   const int turns = (nk + NS - 1) / NS;
-  for (int t = 0; t < turns; ++t) {
-    static_for<NS>([&](auto S) {
-      typedef std::integral_constant<int, (decltype(S)::value + NS - 1) % NS> SN;
-      __builtin_amdgcn_sched_barrier(0);  // no LDS read of the previous tile may sink below the barrier
-      __builtin_amdgcn_s_waitcnt(WAIT_TILE);
-      __builtin_amdgcn_s_barrier();  // every wave's part of this tile is in LDS; the previous tile's slot is free
-      asm volatile("" ::: "memory");  // ... and no LDS read of this tile may be hoisted above it
-      static_for<KSTEPS / 2>([&](auto H) {
-        constexpr int kk = 2 * decltype(H)::value;
-        step(f1, f0, S, SN{}, std::integral_constant<int, kk>{});      // MFMAs of k-step kk - 1 (the previous tile's last when kk == 0)
-        step(f0, f1, S, SN{}, std::integral_constant<int, kk + 1>{});
+  auto main_loop = [&](auto WCS) {
+    for (int t = 0; t < turns; ++t) {
+      static_for<NS>([&](auto S) {
+        typedef std::integral_constant<int, (decltype(S)::value + NS - 1) % NS> SN;
+        __builtin_amdgcn_sched_barrier(0);  // no LDS read of the previous tile may sink below the barrier
+        __builtin_amdgcn_s_waitcnt(WAIT_TILE);
+        __builtin_amdgcn_s_barrier();  // every wave's part of this tile is in LDS; the previous tile's slot is free
+        asm volatile("" ::: "memory");  // ... and no LDS read of this tile may be hoisted above it
+        static_for<KSTEPS / 2>([&](auto H) {
+          constexpr int kk = 2 * decltype(H)::value;
+          step(f1, f0, S, SN{}, std::integral_constant<int, kk>{}, WCS);      // MFMAs of k-step kk - 1 (the previous tile's last when kk == 0)
+          step(f0, f1, S, SN{}, std::integral_constant<int, kk + 1>{}, WCS);
+        });
       });
+    }
+    // the last k-step of the last tile
+    static_for<NM>([&](auto Q) {
+      constexpr int q = decltype(Q)::value, mi = q / NI, ni = q % NI;
+      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[ni], f1.a[mi], acc[mi][ni], 0, 0, 0);
+      if constexpr (decltype(WCS)::value && mi == 0)
+        csum[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[ni], ones, csum[ni], 0, 0, 0);
     });
+  };
+  // (two copies of the loop under one uniform branch, none inside it)
+  if constexpr (CS) {
+    if (do_cs) main_loop(std::true_type{});
+    else main_loop(std::false_type{});
+  } else {
+    main_loop(std::false_type{});
   }
-  // the last k-step of the last tile
-  static_for<NM>([&](auto Q) {
-    constexpr int q = decltype(Q)::value, mi = q / NI, ni = q % NI;
-    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[ni], f1.a[mi], acc[mi][ni], 0, 0, 0);
-  });
   __builtin_amdgcn_s_waitcnt(0x0F70);  // the tail requests (they read nothing) must be done before LDS is reused
   __syncthreads();  // every wave has read its last fragments: LDS can be reused
 
@@ -585,38 +618,46 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   if (m0 + BM <= g.M && n0 + BN <= g.N) store_tile(std::true_type{});
   else store_tile(std::false_type{});
   static_assert(MI <= 4, "at most four 32-row blocks per wave");
+  if constexpr (CS) {
+    // every row of csum holds the column sums: the lanes of row 0 add them to bsum (one workgroup per column
+    // range does, so the add needs no atomic)
+    if (do_cs && (lane & 31) == 0) {
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int col = n0 + wn0 + 32 * j + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (col < g.N) bsum_ptr[col] += csum[j][v];
+        }
+    }
+  }
 }
 
 // explicit instantiations (every tile shape x operand layout the launcher can pick)
-#define DAPPLE_GEMM_INST(BM, BN, WGM, WGN, NS, BK)                                                        \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, false, BK>(GemmArgs, int, int); \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, true, BK>(GemmArgs, int, int);  \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, false, BK>(GemmArgs, int, int);  \
-  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, true, BK>(GemmArgs, int, int);
-DAPPLE_GEMM_INST(256, 256, 2, 2, 2, 64)
+#define DAPPLE_GEMM_INST(BM, BN, WGM, WGN, NS, BK)                                                               \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, false, BK, false>(GemmArgs, int, int); \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, false, true, BK, false>(GemmArgs, int, int);  \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, false, BK, false>(GemmArgs, int, int);  \
+  template __global__ void gemm_mfma_kernel<BM, BN, WGM, WGN, NS, true, true, BK, false>(GemmArgs, int, int);
+DAPPLE_GEMM_INST(256, 256, 2, 2, 4, 32)
 DAPPLE_GEMM_INST(256, 128, 2, 2, 3, 64)
 DAPPLE_GEMM_INST(128, 128, 2, 2, 2, 64)
-DAPPLE_GEMM_INST(128, 128, 2, 2, 4, 64)
-DAPPLE_GEMM_INST(128, 64, 2, 2, 2, 64)
 DAPPLE_GEMM_INST(128, 64, 2, 2, 3, 64)
-DAPPLE_GEMM_INST(128, 64, 2, 2, 4, 64)
-DAPPLE_GEMM_INST(256, 256, 2, 2, 4, 32)
-DAPPLE_GEMM_INST(256, 256, 2, 2, 5, 32)
-DAPPLE_GEMM_INST(256, 128, 2, 2, 6, 32)
+// with the column sum of B: the weight-gradient layout, the two tile shapes the stage's products take
+template __global__ void gemm_mfma_kernel<128, 128, 2, 2, 2, true, true, 64, true>(GemmArgs, int, int);
+template __global__ void gemm_mfma_kernel<128, 64, 2, 2, 3, true, true, 64, true>(GemmArgs, int, int);
 #undef DAPPLE_GEMM_INST
 
 // ------------------------------------------------------------------ host side
-template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS, int BK>
+template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS, int BK, bool CS = false>
 static hipError_t launch_mfma(const GemmArgs& g, hipStream_t st) {
   typedef GemmTile<BM, BN, WGM, WGN, NS, AKS, BKS, BK> CFG;
-  static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, NS, AKS, BKS, BK>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)CFG::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, NS, AKS, BKS, BK, CS>;
+  // once per instantiation, whichever host thread comes first (initialisation of a function-local static is
+  // thread-safe)
+  static const hipError_t attr_rc = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                        (int)CFG::LDS_BYTES);
+  if (attr_rc != hipSuccess) return attr_rc;
   int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   dim3 grid(tiles_m * tiles_n, 1, g.batch);
   hipLaunchKernelGGL(kern, grid, dim3(CFG::NT), CFG::LDS_BYTES, st, g, tiles_m, tiles_n);
@@ -659,40 +700,38 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
   if ((g.epi & (EPI_ADD | EPI_MUL)) && (g.ldaux % 4 || !aligned_to(g.aux, 16))) return false;
   if ((g.epi & EPI_BIAS) && !aligned_to(g.bias, 8)) return false;
   if ((g.epi & EPI_GELU) && !aligned_to(g.C2, 8)) return false;
+  if ((g.epi & EPI_BSUM) && !(g.a_kstrided && g.b_kstrided && g.batch <= 4)) return false;
   return true;
 }
 
 hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;
   if (gemm_uses_mfma(dt, g)) {
-    // a specific configuration: GemmArgs::tile, else the environment variable DAPPLE_GEMM_TILE
-    // (same numbering), for tests and tuning
-    static const int env_tile = [] { const char* e = getenv("DAPPLE_GEMM_TILE"); return e ? atoi(e) : 0; }();
-    switch (g.tile ? g.tile : env_tile) {
-      case 1: return launch_mfma_layout<256, 256, 2, 2, 2>(g, st);
-      case 2: return launch_mfma_layout<256, 128, 2, 2, 3>(g, st);
-      case 3: return launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
-      case 4: return launch_mfma_layout<128, 128, 2, 2, 4>(g, st);
-      case 5: return launch_mfma_layout<128, 64, 2, 2, 2>(g, st);
-      case 6: return launch_mfma_layout<128, 64, 2, 2, 3>(g, st);
-      case 7: return launch_mfma_layout<128, 64, 2, 2, 4>(g, st);
-      case 8: return launch_mfma_layout<256, 256, 2, 2, 4, 32>(g, st);
-      case 9: return launch_mfma_layout<256, 256, 2, 2, 5, 32>(g, st);
-      case 10: return launch_mfma_layout<256, 128, 2, 2, 6, 32>(g, st);
+    const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
+    if (g.epi & EPI_BSUM) {   // the weight-gradient layout (checked above), 128-row tiles only
+      if (g.tile == 3 || (g.tile != 4 && t128 >= 192)) return launch_mfma<128, 128, 2, 2, 2, true, true, 64, true>(g, st);
+      return launch_mfma<128, 64, 2, 2, 3, true, true, 64, true>(g, st);
+    }
+    // GemmArgs::tile names a configuration (tests, timing); 0 = the choice below
+    switch (g.tile) {
+      case 1: return launch_mfma_layout<256, 256, 2, 2, 4, 32>(g, st);
+      case 2: return launch_mfma_layout<256, 128, 2, 2, 3, 64>(g, st);
+      case 3: return launch_mfma_layout<128, 128, 2, 2, 2, 64>(g, st);
+      case 4: return launch_mfma_layout<128, 64, 2, 2, 3, 64>(g, st);
       default: break;
     }
-    // tile choice (measured on the BERT-Large-shaped stage with its three streams running):
-    // 128x128 tiles with two LDS stages when there are at least 192 of them, else 128x64 tiles
-    // with a three-stage ring to keep all CUs busy.  Deeper rings are faster for a product that
-    // runs alone but cost more in co-residency with the other streams' kernels than they gain.
-    // DAPPLE_GEMM_NS_SMALL (2, 3, 4) and DAPPLE_GEMM_NS_MID (2, 4) override the ring depths.
-    long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
-    static const int ns_small = [] { const char* e = getenv("DAPPLE_GEMM_NS_SMALL"); return e ? atoi(e) : 3; }();
-    static const int ns_mid = [] { const char* e = getenv("DAPPLE_GEMM_NS_MID"); return e ? atoi(e) : 2; }();
-    if (t128 > 256) return launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
-    if (t128 >= 192) return ns_mid == 4 ? launch_mfma_layout<128, 128, 2, 2, 4>(g, st) : launch_mfma_layout<128, 128, 2, 2, 2>(g, st);
-    if (ns_small == 2) return launch_mfma_layout<128, 64, 2, 2, 2>(g, st);
-    return ns_small == 4 ? launch_mfma_layout<128, 64, 2, 2, 4>(g, st) : launch_mfma_layout<128, 64, 2, 2, 3>(g, st);
+    // Tile choice.  Every k-tile goes global -> LDS through the compute unit's vector cache at 64 bytes per
+    // clock, against 4096 MFMA flops per clock: a 128x128 tile moves one byte per 64 flops (the two rates just
+    // balance), a 128x64 tile one per 43, a 256x256 tile one per 128.  So: 256x256 tiles (one workgroup per
+    // compute unit, a four-stage ring of 32-wide k-tiles) when they alone fill the chip at least twice;
+    // 128x128 tiles (two workgroups per unit) when there are at least 192 of them; else 128x64 tiles with a
+    // three-stage ring, so that the small products of a stage (2048 x 1024 outputs) still reach every unit.
+    // Measured inside the stage, with its four streams running, the choice between the last two moves the
+    // iteration by less than 2%: what the products wait for there is that global -> LDS path, not the MFMAs.
+    const long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
+    if (t256 >= 512) return launch_mfma_layout<256, 256, 2, 2, 4, 32>(g, st);
+    if (t128 >= 192) return launch_mfma_layout<128, 128, 2, 2, 2, 64>(g, st);
+    return launch_mfma_layout<128, 64, 2, 2, 3, 64>(g, st);
   }
   dim3 blk(32, 8);
   dim3 grid((g.N + 31) / 32, (g.M + 7) / 8, g.batch);

@@ -46,6 +46,10 @@ int dapple_gemm(int dtype, const dapple_gemm_desc* d, void* stream) {
   if ((d->epi & DAPPLE_EPI_BIAS) && !d->bias) return STAGE_E_NULL;
   if ((d->epi & (DAPPLE_EPI_ADD | DAPPLE_EPI_MUL)) && !d->aux) return STAGE_E_NULL;
   if ((d->epi & DAPPLE_EPI_GELU) && !d->C2) return STAGE_E_NULL;
+  if (d->epi & DAPPLE_EPI_BSUM) {
+    if (!d->bsum) return STAGE_E_NULL;
+    if (!d->a_kstrided || !d->b_kstrided || d->batch > 1) return STAGE_E_CONFIG;
+  }
   GemmArgs g{};
   g.A = d->A; g.B = d->B; g.C = d->C; g.C2 = d->C2; g.bias = d->bias; g.aux = d->aux;
   g.M = d->M; g.N = d->N; g.K = d->K; g.lda = d->lda; g.ldb = d->ldb; g.ldc = d->ldc; g.ldaux = d->ldaux;
@@ -53,7 +57,7 @@ int dapple_gemm(int dtype, const dapple_gemm_desc* d, void* stream) {
   g.kseg_len = d->kseg_len ? d->kseg_len : d->K; g.segA = d->segA; g.segB = d->segB;
   g.batch = d->batch ? d->batch : 1; g.sA = d->sA; g.sB = d->sB; g.sC = d->sC; g.sBias = d->sBias;
   g.k_valid = d->k_valid ? d->k_valid : d->K; g.epi = d->epi; g.tile = d->tile;
-  g.m_valid = d->M; g.n_valid = d->N;
+  g.m_valid = d->M; g.n_valid = d->N; g.bsum_z[0] = d->bsum;
   if (g.K % g.kseg_len) return STAGE_E_CONFIG;
   Dtype dt = dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32;
   int mfma = gemm_uses_mfma(dt, g) ? 1 : 0;

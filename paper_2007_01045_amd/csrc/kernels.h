@@ -23,7 +23,8 @@ enum GemmEpi {
   EPI_GELU = 8,   // C = gelu(t), C2 = gelu'(t)
   EPI_ACC32 = 16,  // C is fp32 and C += t (weight-gradient accumulation)
   EPI_OUT32 = 32,  // C is fp32 and C = t
-  EPI_AUX32 = 64   // aux is fp32 (residual stream of a bf16 stage)
+  EPI_AUX32 = 64,  // aux is fp32 (residual stream of a bf16 stage)
+  EPI_BSUM = 128   // bsum[n] += sum_k B(n,k): the bias gradient rides along with the weight gradient
 };
 
 struct GemmArgs {
@@ -46,10 +47,12 @@ struct GemmArgs {
   const void* Az[4];
   const void* Bz[4];
   void* Cz[4];
+  // EPI_BSUM: fp32 [N] per instance (a NULL entry skips that instance); both operands k-strided
+  float* bsum_z[4];
   int k_valid;  // k-strided operands: rows k >= k_valid read as zero (K itself is padded)
   int m_valid, n_valid;  // rows of A / B that exist in memory (0 = M / N); rows beyond read as zero
   int epi;
-  int tile;  // 0 = automatic choice; 1..7 = a specific tile shape / ring depth (see launch_gemm)
+  int tile;  // 0 = automatic choice; 1..4 = a specific tile shape / ring depth (see launch_gemm)
 };
 
 hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st);

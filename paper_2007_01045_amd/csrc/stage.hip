@@ -73,7 +73,7 @@ struct Layout {
   int NP = 0, VP = 0;
   size_t sh_rows = 0, sh_tgt = 0, sh_r = 0, sh_gl = 0, sh_glp = 0, sh_st = 0, sh_t = 0, sh_dz = 0;
   size_t wh_logits = 0, wh_rowloss = 0, wh_dt = 0, wh_dgl = 0, wh_dh = 0, wh_dr = 0, wh_dyfull = 0, wh_part = 0,
-         wh_part_cz = 0, wh_part_ch = 0, wh_info = 0;
+         wh_part_cz = 0, wh_info = 0;
   size_t wh_logits2 = 0, wh_rowloss2 = 0, wh_info2 = 0;  // second set: the forward re-run inside a backward task
   size_t we_dx0 = 0, we_de = 0, we_part = 0;
   // fp32 copies of LayerNorm outputs for the residual adds (bf16 stages); set 1: the forward re-run
@@ -88,8 +88,7 @@ struct Layout {
   // workspace (bytes)
   // buffers the side stream reads exist twice (layers alternate between the sets)
   size_t ws_dx[2] = {0, 0}, ws_dz2[2] = {0, 0}, ws_du[2] = {0, 0}, ws_dy1 = 0, ws_dz1[2] = {0, 0}, ws_dctx = 0,
-         ws_dqkv[2] = {0, 0}, ws_delta = 0, ws_part_ln2[2] = {0, 0}, ws_part_ln1[2] = {0, 0}, ws_part_du[2] = {0, 0},
-         ws_part_qkv[2] = {0, 0}, ws_head = 0;
+         ws_dqkv[2] = {0, 0}, ws_delta = 0, ws_part_ln2[2] = {0, 0}, ws_part_ln1[2] = {0, 0}, ws_head = 0;
   size_t workspace_bytes = 0;
   // arena
   size_t grad_bytes = 0, arena_grads = 0, arena_slots = 0, arena_ws = 0, arena_bytes = 0;
@@ -188,7 +187,6 @@ void build_layout(const stage_config& c, Layout& L) {
   for (int p = 0; p < 2; ++p) {
     L.ws_dz2[p] = wtake(U); L.ws_du[p] = wtake(T * F * E); L.ws_dz1[p] = wtake(U); L.ws_dqkv[p] = wtake(3 * U);
     L.ws_part_ln2[p] = wtake(ln_part); L.ws_part_ln1[p] = wtake(ln_part);
-    L.ws_part_du[p] = wtake(cs_rows * F * 4); L.ws_part_qkv[p] = wtake(cs_rows * 3 * H * 4);
   }
   if (c.has_mlm_head) {
     const size_t NP = L.NP, VP = L.VP;
@@ -197,7 +195,7 @@ void build_layout(const stage_config& c, Layout& L) {
     size_t lp = ((NP + 7) / 8) * 3 * H * 4, cp = ((NP + 63) / 64) * VP * 4;
     // three partial-sum buffers: the LayerNorm backward writes its own on the backward stream while the side
     // stream is still reducing a column sum
-    L.wh_part = wtake(lp); L.wh_part_cz = wtake(cp); L.wh_part_ch = wtake(((NP + 63) / 64) * H * 4); L.wh_info = wtake(16);
+    L.wh_part = wtake(lp); L.wh_part_cz = wtake(cp); L.wh_info = wtake(16);
     if (L.recompute) { L.wh_logits2 = wtake(NP * VP * 4); L.wh_rowloss2 = wtake(NP * 4); L.wh_info2 = wtake(16); }
   }
   if (c.has_embedding) {
@@ -218,11 +216,9 @@ void build_layout(const stage_config& c, Layout& L) {
   L.arena_bytes = L.arena_ws + L.ws_copies * L.workspace_bytes;
 }
 
-struct ProfEvent { hipEvent_t a, b; int cls; double flops; int lane; };
+struct ProfEvent { hipEvent_t a, b; int cls; double flops; int lane; int M, N, K, batch; };
 
 }  // namespace
-
-static int envi(const char* name) { const char* e = getenv(name); return e ? atoi(e) : 0; }
 
 struct dapple_stage {
   stage_config cfg;
@@ -233,10 +229,8 @@ struct dapple_stage {
   char* arena;
   float* grads;
   hipStream_t st;         // the caller's stream: the critical path (forward; backward data gradients)
-  // library-owned: weight / bias / LayerNorm gradient work of a backward task.  side2 == side unless
-  // DAPPLE_SIDE_LANES=2; then each gradient tensor is always on the same one of the two (side: W2, b2,
-  // ln2, W1, b1; side2: ln1, bo, Wq..Wo, bq..bv), so the updates of any one tensor stay in task order
-  hipStream_t side = nullptr, side2 = nullptr;
+  // library-owned: weight / bias / LayerNorm gradient work of every backward task, in task order
+  hipStream_t side = nullptr;
   hipStream_t fwd = nullptr;   // library-owned: forward tasks inside stage_run_schedule
   hipStream_t bwd2 = nullptr;  // library-owned: every second backward task inside stage_run_schedule
   hipEvent_t ev_b2done = nullptr;
@@ -250,7 +244,7 @@ struct dapple_stage {
   std::vector<hipEvent_t> ev_f, ev_b;  // per slot: forward done (fwd lane), backward done (caller's stream)
   hipEvent_t ev_start = nullptr;
   bool serial = false, no_side = false;
-  std::vector<hipEvent_t> ev;  // per layer: 4 "inputs ready" events (main -> side) + 2 "layer done" (each side stream -> main)
+  std::vector<hipEvent_t> ev;  // per layer: 4 "inputs ready" events (main -> side) + 1 "layer done" (side -> main)
   std::vector<int> slot_of_mb;   // slot -> micro-batch id, -1 = free
   int live = 0, peak_live = 0;
   uint64_t fwd_tasks = 0, bwd_tasks = 0, launches = 0;
@@ -272,29 +266,25 @@ struct dapple_stage {
   // main -> side: the side stream may start once the main stream has passed this point
   int fork(int layer, int which) {
     if (dry) return STAGE_OK;
-    hipEvent_t e = ev[layer * 6 + which];
-    if (hipEventRecord(e, cur) != hipSuccess || hipStreamWaitEvent(which < 2 ? side : side2, e, 0) != hipSuccess)
+    hipEvent_t e = ev[layer * 5 + which];
+    if (hipEventRecord(e, cur) != hipSuccess || hipStreamWaitEvent(side, e, 0) != hipSuccess)
       return fail(STAGE_E_DEVICE, "event record / wait failed");
     return STAGE_OK;
   }
   // side -> main, in two halves: mark the side work of a layer done; later make main wait for it
   int side_done(int layer) {
     if (dry) return STAGE_OK;
-    if (hipEventRecord(ev[layer * 6 + 4], side) != hipSuccess ||
-        (side2 != side && hipEventRecord(ev[layer * 6 + 5], side2) != hipSuccess))
-      return fail(STAGE_E_DEVICE, "event record failed");
+    if (hipEventRecord(ev[layer * 5 + 4], side) != hipSuccess) return fail(STAGE_E_DEVICE, "event record failed");
     return STAGE_OK;
   }
   int join(int layer) {
     if (dry) return STAGE_OK;
-    if (hipStreamWaitEvent(cur, ev[layer * 6 + 4], 0) != hipSuccess ||
-        (side2 != side && hipStreamWaitEvent(cur, ev[layer * 6 + 5], 0) != hipSuccess))
-      return fail(STAGE_E_DEVICE, "event wait failed");
+    if (hipStreamWaitEvent(cur, ev[layer * 5 + 4], 0) != hipSuccess) return fail(STAGE_E_DEVICE, "event wait failed");
     return STAGE_OK;
   }
 
   template <typename Fn>
-  int run_on(hipStream_t stream, int cls, double flops, Fn&& fn) {
+  int run_on(hipStream_t stream, int cls, double flops, Fn&& fn, const GemmArgs* shape = nullptr) {
     if (dry) { ++launches; return STAGE_OK; }
     ProfEvent* pe = nullptr;
     if (profiling) {
@@ -306,6 +296,7 @@ struct dapple_stage {
       }
       pe = &events[events_used++];
       pe->cls = cls; pe->flops = flops; pe->lane = stream == st ? 0 : (stream == side ? 1 : (stream == fwd ? 2 : (stream == bwd2 ? 3 : 4)));
+      pe->M = shape ? shape->M : 0; pe->N = shape ? shape->N : 0; pe->K = shape ? shape->K : 0; pe->batch = shape ? shape->batch : 0;
       (void)hipEventRecord(pe->a, stream);
     }
     hipError_t e = fn(stream);
@@ -315,27 +306,15 @@ struct dapple_stage {
     return STAGE_OK;
   }
 
-  int gemm(int cls, GemmArgs g, hipStream_t stream = nullptr, bool on_side = false, bool second_side = false) {
+  int gemm(int cls, GemmArgs g, bool on_side = false) {
     if (g.kseg_len == 0) g.kseg_len = g.K;
     if (g.k_valid == 0) g.k_valid = g.K;
     if (g.m_valid == 0) g.m_valid = g.M;
     if (g.n_valid == 0) g.n_valid = g.N;
     if (g.batch == 0) g.batch = 1;
     double flops = 2.0 * g.M * g.N * (double)g.K * g.batch;
-    hipStream_t s_ = on_side ? (second_side ? side2 : side) : cur;
-    {  // tuning: DAPPLE_TILE_<lane>_<BIG|MID|SMALL> picks the tile configuration per lane and size class
-      static const int tab[3][3] = {
-          {envi("DAPPLE_TILE_MAIN_BIG"), envi("DAPPLE_TILE_MAIN_MID"), envi("DAPPLE_TILE_MAIN_SMALL")},
-          {envi("DAPPLE_TILE_SIDE_BIG"), envi("DAPPLE_TILE_SIDE_MID"), envi("DAPPLE_TILE_SIDE_SMALL")},
-          {envi("DAPPLE_TILE_FWD_BIG"), envi("DAPPLE_TILE_FWD_MID"), envi("DAPPLE_TILE_FWD_SMALL")}};
-      const int lane = (s_ == st || s_ == bwd2) ? 0 : ((s_ == side || s_ == side2) ? 1 : 2);
-      const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
-      const int cl = t128 > 256 ? 0 : (t128 >= 192 ? 1 : 2);
-      if (!g.tile) g.tile = tab[lane][cl];
-      static const int deep[3] = {envi("DAPPLE_TILE_MAIN_DEEP"), envi("DAPPLE_TILE_SIDE_DEEP"), envi("DAPPLE_TILE_FWD_DEEP")};
-      if (cl == 2 && g.K >= 2048 && deep[lane]) g.tile = deep[lane];  // few tiles, long K
-    }
-    return run_on(s_, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); });
+    hipStream_t s_ = on_side ? side : cur;
+    return run_on(s_, cls, flops, [&](hipStream_t s) { return launch_gemm(dt, g, s); }, &g);
   }
 
   // sl: where the task's activations live; fs: forward workspace set
@@ -480,13 +459,13 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     // The head's accumulator updates go to the side stream like the layers' (fork events of the pseudo-layer
     // n_layers), in the order dE_out, db_out, LayerNorm gain and shift, dWt, dbt.
     const int HL = cfg.n_layers;
-    float *part_cz = (float*)ws(L.wh_part_cz), *part_ch = (float*)ws(L.wh_part_ch);
+    float* part_cz = (float*)ws(L.wh_part_cz);
     TRY(fork(HL, 0));
     {  // dE_out += dz^T t
       GemmArgs ga{};
       ga.A = dz; ga.lda = VP; ga.a_kstrided = 1; ga.B = t; ga.ldb = H; ga.b_kstrided = 1;
       ga.C = gr(L.hEout); ga.ldc = H; ga.M = V; ga.N = H; ga.K = NP; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_HEAD, ga, nullptr, true));
+      TRY(gemm(KC_HEAD, ga, true));
     }
     TRY(run_on(side, KC_HEAD, 0, [&](hipStream_t q) { return launch_colsum(dt, dz, NP, V, VP, part_cz, gr(L.hbout), 1, 0, 0, q); }));
     {  // dt = dz E_out
@@ -500,13 +479,13 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     TRY(run_on(side, KC_HEAD, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.hG), gr(L.hB), nullptr, q); }));
     TRY(run(KC_HEAD, 0, [&](hipStream_t q) { return launch_mul(dt, dgl, glp, dh, (long)NP * H, q); }));
     TRY(fork(HL, 0));   // event 0 again: the side stream's first wait on it is already enqueued
-    {  // dWt += r^T dh
+    {  // dWt += r^T dh, dbt += the column sums of dh
       GemmArgs ga{};
       ga.A = r; ga.lda = H; ga.a_kstrided = 1; ga.B = dh; ga.ldb = H; ga.b_kstrided = 1;
-      ga.C = gr(L.hWt); ga.ldc = H; ga.M = H; ga.N = H; ga.K = NP; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_HEAD, ga, nullptr, true));
+      ga.C = gr(L.hWt); ga.ldc = H; ga.M = H; ga.N = H; ga.K = NP; ga.epi = EPI_ACC32 | EPI_BSUM;
+      ga.bsum_z[0] = gr(L.hbt);
+      TRY(gemm(KC_HEAD, ga, true));
     }
-    TRY(run_on(side, KC_HEAD, 0, [&](hipStream_t q) { return launch_colsum(dt, dh, NP, H, H, part_ch, gr(L.hbt), 1, 0, 0, q); }));
     TRY(side_done(HL));
     {  // dr = dh Wt^T
       GemmArgs ga{};
@@ -522,8 +501,7 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     const LayerStash& a = L.ls[l];
     const int ps = l & 1;  // workspace set of this layer
     char *dz2 = ws(L.ws_dz2[ps]), *du = ws(L.ws_du[ps]), *dz1 = ws(L.ws_dz1[ps]), *dqkv = ws(L.ws_dqkv[ps]);
-    float *part_ln2 = (float*)ws(L.ws_part_ln2[ps]), *part_ln1 = (float*)ws(L.ws_part_ln1[ps]),
-          *part_du = (float*)ws(L.ws_part_du[ps]), *part_qkv = (float*)ws(L.ws_part_qkv[ps]);
+    float *part_ln2 = (float*)ws(L.ws_part_ln2[ps]), *part_ln1 = (float*)ws(L.ws_part_ln1[ps]);
     const char* xl = l == 0 ? sl + L.slot_x0 : sl + L.ls[l - 1].y;
     char *qkv = sl + a.qkv, *ctx = sl + a.ctx, *z1 = sl + a.z1, *y1 = sl + a.y1, *gp = sl + a.gp, *g = sl + a.g,
          *z2 = sl + a.z2;
@@ -541,15 +519,12 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     // launch after the last weight-gradient product (the side stream is the longest chain of a
     // step, and a small kernel costs it a dispatch of ~15 us when the GPU is full).  Each
     // reduction adds in the same order as the stand-alone kernels.
-    const bool merged = side2 == side;
     const int nblk_ln2 = nblk;
-    if (!merged)
-      TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln2, nblk, 3, H, gr(p.ln2g), gr(p.ln2b), gr(p.b2), q); }));
     {  // dW2 += g^T dz2
       GemmArgs ga{};
       ga.A = g; ga.lda = F; ga.a_kstrided = 1; ga.B = dz2; ga.ldb = H; ga.b_kstrided = 1;
       ga.C = gr(p.W2); ga.ldc = H; ga.M = F; ga.N = H; ga.K = T; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_GEMM_WGRAD, ga, nullptr, true));
+      TRY(gemm(KC_GEMM_WGRAD, ga, true));
     }
     {  // du = (dz2 W2^T) o GELU'(u)
       GemmArgs ga{};
@@ -558,16 +533,12 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
     TRY(fork(l, 1));
-    int nblk_du = 0, ps_du = 0;
-    if (merged)
-      TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_colsum_partials(dt, du, T, F, F, part_du, 1, 0, &nblk_du, &ps_du, q); }));
-    else
-      TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_colsum(dt, du, T, F, F, part_du, gr(p.b1), 1, 0, 0, q); }));
-    {  // dW1 += y1^T du
+    {  // dW1 += y1^T du, and db1 += the column sums of du in the same launch
       GemmArgs ga{};
       ga.A = y1; ga.lda = H; ga.a_kstrided = 1; ga.B = du; ga.ldb = F; ga.b_kstrided = 1;
-      ga.C = gr(p.W1); ga.ldc = F; ga.M = H; ga.N = F; ga.K = T; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_GEMM_WGRAD, ga, nullptr, true));
+      ga.C = gr(p.W1); ga.ldc = F; ga.M = H; ga.N = F; ga.K = T; ga.epi = EPI_ACC32 | EPI_BSUM;
+      ga.bsum_z[0] = gr(p.b1);
+      TRY(gemm(KC_GEMM_WGRAD, ga, true));
     }
     {  // dy1 = du W1^T + dz2 (residual branch)
       GemmArgs ga{};
@@ -578,8 +549,6 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dy1, z1, dt == DT_BF16, st1, w(p.ln1g), dz1, part_ln1, &nblk, T, H, q); }));
     TRY(fork(l, 2));
     const int nblk_ln1 = nblk;
-    if (!merged)
-      TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) { return launch_partial_reduce(part_ln1, nblk, 3, H, gr(p.ln1g), gr(p.ln1b), gr(p.bo), q); }));
     {  // dctx = dz1 Wo^T
       GemmArgs ga{};
       ga.A = dz1; ga.lda = H; ga.B = w(p.Wo); ga.ldb = H; ga.C = dctx; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H;
@@ -595,28 +564,21 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       TRY(run(KC_ATTN_BWD, fl, [&](hipStream_t q) { return launch_attn_bwd(dt, aa, q); }));
     }
     TRY(fork(l, 3));
-    int nblk_q = 0, ps_q = 0;
-    if (merged)
-      TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) {
-        return launch_colsum_partials(dt, dqkv, T, H, H, part_qkv, 3, (long)T * H, &nblk_q, &ps_q, q);
-      }));
-    else
-      TRY(run_on(side2, KC_REDUCE, 0, [&](hipStream_t q) {
-        return launch_colsum(dt, dqkv, T, H, H, part_qkv, gr(p.bq), 3, (long)T * H, (long)pstride, q);
-      }));
     {  // dWq, dWk, dWv += x^T dq, x^T dk, x^T dv and dWo += ctx^T dz1: four products of one
-       // shape in one launch (alone, each would leave most of the CUs idle)
+       // shape in one launch (alone, each would leave most of the CUs idle); the first three
+       // also add the column sums of dq, dk, dv to the bias gradients
       GemmArgs ga{};
       ga.lda = H; ga.a_kstrided = 1; ga.ldb = H; ga.b_kstrided = 1;
-      ga.ldc = H; ga.M = H; ga.N = H; ga.K = T; ga.batch = 4; ga.epi = EPI_ACC32;
+      ga.ldc = H; ga.M = H; ga.N = H; ga.K = T; ga.batch = 4; ga.epi = EPI_ACC32 | EPI_BSUM;
       for (int z = 0; z < 3; ++z) {
         ga.Az[z] = xl; ga.Bz[z] = dqkv + z * U; ga.Cz[z] = gr(p.Wq + z * pstride);
+        ga.bsum_z[z] = gr(p.bq + z * pstride);
       }
       ga.Az[3] = ctx; ga.Bz[3] = dz1; ga.Cz[3] = gr(p.Wo);
       ga.A = ga.Az[0]; ga.B = ga.Bz[0]; ga.C = ga.Cz[0];
-      TRY(gemm(KC_GEMM_WGRAD, ga, nullptr, true, true));
+      TRY(gemm(KC_GEMM_WGRAD, ga, true));
     }
-    if (merged) {
+    {
       ReduceJobs J{};
       auto add = [&](const float* partial, long stride, int nb, int cols, float* out) {
         J.j[J.n++] = ReduceJob{partial, out, nb, cols, stride};
@@ -624,9 +586,7 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       float* o2[3] = {gr(p.ln2g), gr(p.ln2b), gr(p.b2)};
       float* o1[3] = {gr(p.ln1g), gr(p.ln1b), gr(p.bo)};
       for (int v = 0; v < 3; ++v) add(part_ln2 + (size_t)v * H, 3L * H, nblk_ln2, H, o2[v]);
-      add(part_du, ps_du, nblk_du, F, gr(p.b1));
       for (int v = 0; v < 3; ++v) add(part_ln1 + (size_t)v * H, 3L * H, nblk_ln1, H, o1[v]);
-      for (int z = 0; z < 3; ++z) add(part_qkv + (size_t)z * nblk_q * ps_q, ps_q, nblk_q, H, gr(p.bq) + (size_t)z * pstride);
       TRY(run_on(side, KC_REDUCE, 0, [&](hipStream_t q) { return launch_reduce_jobs(J, q); }));
     }
     TRY(side_done(l));
@@ -651,8 +611,8 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     // other accumulator update, so that backward tasks may run on two lanes: fork event 3 of layer 0 is free
     // again (its side work was enqueued above), and the task's closing join below waits for this too
     TRY(fork(0, 3));
-    TRY(run_on(side2, KC_EMBED, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.embG), gr(L.embB), nullptr, q); }));
-    TRY(run_on(side2, KC_EMBED, 0, [&](hipStream_t q) {
+    TRY(run_on(side, KC_EMBED, 0, [&](hipStream_t q) { return launch_partial_reduce(part, nblk, 3, H, gr(L.embG), gr(L.embB), nullptr, q); }));
+    TRY(run_on(side, KC_EMBED, 0, [&](hipStream_t q) {
       return launch_embed_bwd(dt, (const int32_t*)(sl + L.slot_ids), de, gr(L.embEw), gr(L.embEp), cfg.micro_batch,
                               cfg.seq, H, cfg.vocab, q);
     }));
@@ -768,33 +728,19 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
   h->slot_of_mb.assign(cfg->max_slots, -1);
   if (!dry) {
     // default priority on purpose; the side stream never outlives the handle
-    // DAPPLE_SERIAL=1 (a debugging switch) puts every kernel on the caller's stream
-    {
-      const char* e = getenv("DAPPLE_SERIAL");   // 1: no side lane and no forward lane; 2: no forward lane; 3: no side lane
-      int v = e ? atoi(e) : 0;
-      h->serial = v == 1 || v == 2 || (cfg->flags & STAGE_FLAG_ONE_STREAM);
-      h->no_side = v == 1 || v == 3 || (cfg->flags & STAGE_FLAG_ONE_STREAM);
-    }
+    h->serial = h->no_side = (cfg->flags & STAGE_FLAG_ONE_STREAM) != 0;
     if (h->no_side) {
-      h->side = h->side2 = h->st;
+      h->side = h->st;
     } else {
       hipError_t e = make_lane(h->st, &h->side);
       if (e != hipSuccess) {
         delete h;
         return fail(STAGE_E_DEVICE, "creating the side stream failed: %s", hipGetErrorString(e));
       }
-      // one side stream by default: a second one (DAPPLE_SIDE_LANES=2) takes more from the backward
-      // lanes than it gives (measured 1957 against 2108 samples/s on the BERT-Large-shaped stage)
-      if (envi("DAPPLE_SIDE_LANES") != 2) {
-        h->side2 = h->side;
-      } else if (make_lane(h->st, &h->side2) != hipSuccess) {
-        delete h;
-        return fail(STAGE_E_DEVICE, "hipStreamCreate failed");
-      }
     }
     // the forward lane and the second backward lane are made by the first stage_run_schedule that uses lanes:
     // a stage driven task by task (stage_fwd / stage_bwd, the pipeline of several stages) holds no idle queues
-    h->ev.resize((size_t)(cfg->n_layers + 1) * 6);   // one more set for the head's side work
+    h->ev.resize((size_t)(cfg->n_layers + 1) * 5);   // one more set for the head's side work
     h->ev_f.resize(cfg->max_slots);
     h->ev_b.resize(cfg->max_slots);
     std::vector<hipEvent_t*> all;
@@ -826,7 +772,6 @@ int stage_destroy(stage_handle h) {
   if (!h->dry) {
     (void)hipStreamSynchronize(h->st);
     if (h->side) (void)hipStreamSynchronize(h->side);
-    if (h->side2) (void)hipStreamSynchronize(h->side2);
     if (h->fwd) (void)hipStreamSynchronize(h->fwd);
     if (h->bwd2) (void)hipStreamSynchronize(h->bwd2);
   }
@@ -839,7 +784,6 @@ int stage_destroy(stage_handle h) {
   if (h->ev_start) (void)hipEventDestroy(h->ev_start);
   if (h->ev_b2done) (void)hipEventDestroy(h->ev_b2done);
   if (h->bwd2) (void)hipStreamDestroy(h->bwd2);
-  if (h->side2 && h->side2 != h->side && h->side2 != h->st) (void)hipStreamDestroy(h->side2);
   if (h->side && h->side != h->st) (void)hipStreamDestroy(h->side);
   if (h->fwd) (void)hipStreamDestroy(h->fwd);
   delete h;
@@ -954,7 +898,7 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
   // themselves and backwards among themselves in list order (which fixes the order of every
   // gradient accumulation).  The early-backward order needs no more than that; the other orders
   // are run strictly as listed (a backward waits for every forward listed before it).
-  const bool lanes = !h->dry && (!h->profiling || getenv("DAPPLE_TIMELINE")) && !h->serial;
+  const bool lanes = !h->dry && !h->profiling && !h->serial;
   const bool strict = order != STAGE_ORDER_EARLY_BACKWARD;
   std::vector<char> b_pending(h->cfg.max_slots, 0);
   int last_f_slot = -1;
@@ -966,11 +910,10 @@ int stage_run_schedule(stage_handle h, int M, int K, int order, const void* cons
   // A capture keeps to one backward lane: the HIP runtime that ships with PyTorch 2.10 (ROCm 7.0) recurses
   // without end in hipStreamEndCapture once two streams other than the capture's origin have waited for each
   // other's events (side lane <-> second backward lane); the origin may wait for and be waited for by anyone.
-  static const int bwd_lanes_env = envi("DAPPLE_BWD_LANES");
   // (The GPipe order alternates its backward tasks the same way once every forward is done; an explicit list
   // keeps one backward lane.)
   const bool two = lanes && order != STAGE_ORDER_EXPLICIT && h->L.ws_copies == 2 &&
-                   !h->no_side && bwd_lanes_env != 1 && !h->capturing;
+                   !h->no_side && !h->capturing;
   int n_bwd = 0;
   bool used_b2 = false;
   if (lanes) TRY(ensure_lanes(h));
@@ -1144,8 +1087,7 @@ int stage_reset_stats(stage_handle h) {
 
 int stage_profile_enable(stage_handle h, int on) {
   if (!h) return fail(STAGE_E_NULL, "handle is NULL");
-  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess ||
-                  hipStreamSynchronize(h->side2) != hipSuccess))
+  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
   h->profiling = on != 0;
   h->events_used = 0;
@@ -1154,26 +1096,11 @@ int stage_profile_enable(stage_handle h, int on) {
 
 int stage_profile_read(stage_handle h, int n, uint64_t* launches, double* ms, double* flops) {
   if (!h || !launches || !ms || !flops) return fail(STAGE_E_NULL, "arguments must not be NULL");
-  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess ||
-                  hipStreamSynchronize(h->side2) != hipSuccess))
+  if (!h->dry && (hipStreamSynchronize(h->st) != hipSuccess || hipStreamSynchronize(h->side) != hipSuccess))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
   if (!h->dry && h->fwd && (hipStreamSynchronize(h->fwd) != hipSuccess || (h->bwd2 && hipStreamSynchronize(h->bwd2) != hipSuccess)))
     return fail(STAGE_E_DEVICE, "stream synchronise failed");
   for (int i = 0; i < n; ++i) { launches[i] = 0; ms[i] = 0; flops[i] = 0; }
-  if (const char* path = getenv("DAPPLE_TIMELINE")) {
-    // debugging aid: every launch of the profiled steps as "class,lane,start_ms,end_ms" (lane 0 = caller's
-    // stream, 1 = side, 2 = forward), times relative to the first launch
-    if (FILE* f = fopen(path, "w")) {
-      for (size_t i = 0; i < h->events_used; ++i) {
-        const ProfEvent& e = h->events[i];
-        float t0 = 0.f, t1 = 0.f;
-        (void)hipEventElapsedTime(&t0, h->events[0].a, e.a);
-        (void)hipEventElapsedTime(&t1, h->events[0].a, e.b);
-        fprintf(f, "%s,%d,%.4f,%.4f\n", kClassNames[e.cls], e.lane, t0, t1);
-      }
-      fclose(f);
-    }
-  }
   for (size_t i = 0; i < h->events_used; ++i) {
     const ProfEvent& e = h->events[i];
     if (e.cls >= n) continue;
@@ -1185,6 +1112,25 @@ int stage_profile_read(stage_handle h, int n, uint64_t* launches, double* ms, do
   return STAGE_OK;
 }
 
+int stage_profile_launches(stage_handle h, stage_launch_record* out, int capacity) {
+  if (!h || !out) return fail(STAGE_E_NULL, "handle and out must not be NULL");
+  if (!h->dry) {
+    hipError_t e = hipStreamSynchronize(h->st);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->side);
+    if (e == hipSuccess && h->fwd) e = hipStreamSynchronize(h->fwd);
+    if (e == hipSuccess && h->bwd2) e = hipStreamSynchronize(h->bwd2);
+    if (e != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed: %s", hipGetErrorString(e));
+  }
+  int n = 0;
+  for (size_t i = 0; i < h->events_used && n < capacity; ++i, ++n) {
+    const ProfEvent& e = h->events[i];
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, e.a, e.b) != hipSuccess) return fail(STAGE_E_DEVICE, "hipEventElapsedTime failed");
+    out[n] = stage_launch_record{e.cls, e.lane, e.M, e.N, e.K, e.batch, (double)t, e.flops};
+  }
+  return n;
+}
+
 const char* stage_profile_class_name(int i) { return (i >= 0 && i < KC_COUNT) ? kClassNames[i] : nullptr; }
 
 int stage_sync(stage_handle h) {
@@ -1192,7 +1138,6 @@ int stage_sync(stage_handle h) {
   if (h->dry) return STAGE_OK;
   hipError_t e = hipStreamSynchronize(h->st);
   if (e == hipSuccess) e = hipStreamSynchronize(h->side);
-  if (e == hipSuccess) e = hipStreamSynchronize(h->side2);
   if (e != hipSuccess) return fail(STAGE_E_DEVICE, "stream synchronise failed: %s", hipGetErrorString(e));
   if (h->cfg.has_mlm_head) {
     int32_t info[2] = {0, 0};
