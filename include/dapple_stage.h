@@ -81,10 +81,11 @@ enum {
   STAGE_FLAG_RECOMPUTE = 2, /* re-computation (section VI-E, Table VI's "+ RC" rows): a resident
                                micro-batch keeps only the stage's input (token ids on a first stage)
                                and its targets; stage_bwd re-runs the forward from them before it goes
-                               backward.  slot_bytes shrinks to that; two activation buffers of the
-                               full size (one for the forward tasks, one for the backward tasks) are
-                               part of workspace_bytes.  Gradients and outputs are bit-identical to
-                               the stage without the flag. */
+                               backward.  slot_bytes shrinks to that; activation buffers of the full
+                               size -- one for the forward tasks and one per backward lane (two lanes;
+                               one with STAGE_FLAG_ONE_STREAM) -- are part of the arena and of
+                               peak_activation_bytes, whatever K and M are.  Gradients and outputs are
+                               bit-identical to the stage without the flag. */
   STAGE_FLAG_ONE_STREAM = 4 /* every kernel goes on the stage's own stream: no library-owned lanes.
                                For a stage that is one of several run beside each other
                                (dapple_pipeline.h), where the overlap comes from the other stages and
@@ -112,14 +113,15 @@ typedef struct {
   uint64_t grad_bytes;      /* fp32 accumulators */
   uint64_t slot_bytes;      /* activations one resident micro-batch keeps from F to B */
   uint64_t workspace_bytes; /* transient buffers shared by all tasks (one copy) */
-  uint64_t arena_bytes;     /* grad_bytes + max_slots * slot_bytes + copies * workspace_bytes (+ alignment);
-                               copies = 2 (one workspace per backward lane), 1 under STAGE_FLAG_RECOMPUTE */
+  uint64_t arena_bytes;     /* grad_bytes + max_slots * slot_bytes + copies * workspace_bytes (+ alignment, + the
+                               forward tasks' activation buffer under STAGE_FLAG_RECOMPUTE); copies = 2 (one
+                               workspace per backward lane), 1 under STAGE_FLAG_ONE_STREAM */
 } stage_sizes;
 
 typedef struct {
   uint64_t slot_bytes;
-  uint64_t peak_activation_bytes; /* peak_live_slots * slot_bytes (+ the two activation buffers
-                                     under STAGE_FLAG_RECOMPUTE) */
+  uint64_t peak_activation_bytes; /* peak_live_slots * slot_bytes (+ the activation buffers of
+                                     STAGE_FLAG_RECOMPUTE: forward tasks' + one per backward lane) */
   int32_t live_slots, peak_live_slots;
   uint64_t fwd_tasks, bwd_tasks, kernel_launches;
 } stage_stats_t;

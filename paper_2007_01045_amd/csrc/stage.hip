@@ -81,10 +81,11 @@ struct Layout {
   size_t ws_y1f[2] = {0, 0}, ws_yf[2][2] = {{0, 0}, {0, 0}};
   size_t slot_bytes = 0;
   // re-computation: a resident micro-batch keeps only its input (and targets); the activations of
-  // the task being run live in one of two buffers of act_bytes (0: forward tasks, 1: backward tasks)
+  // the task being run live in a buffer of act_bytes: one for forward tasks (arena_fwd_act) and one
+  // per backward lane (ws_act, inside each copy of the workspace)
   bool recompute = false;
   int ws_copies = 1;
-  size_t act_bytes = 0, st_x = 0, st_aux = 0, ws_act[2] = {0, 0}, ws_ydummy = 0;
+  size_t act_bytes = 0, st_x = 0, st_aux = 0, ws_act = 0, ws_ydummy = 0, arena_fwd_act = 0;
   // workspace (bytes)
   // buffers the side stream reads exist twice (layers alternate between the sets)
   size_t ws_dx[2] = {0, 0}, ws_dz2[2] = {0, 0}, ws_du[2] = {0, 0}, ws_dy1 = 0, ws_dz1[2] = {0, 0}, ws_dctx = 0,
@@ -202,17 +203,18 @@ void build_layout(const stage_config& c, Layout& L) {
     L.we_dx0 = wtake(U); L.we_de = wtake(U); L.we_part = wtake(ln_part);
   }
   if (L.recompute) {
-    L.ws_act[0] = wtake(L.act_bytes); L.ws_act[1] = wtake(L.act_bytes); L.ws_ydummy = wtake(U);
+    L.ws_act = wtake(L.act_bytes); L.ws_ydummy = wtake(U);
   }
   L.workspace_bytes = wo;
 
   L.grad_bytes = align_up(L.n_params * 4);
   L.arena_grads = 0;
   L.arena_slots = L.grad_bytes;
-  L.arena_ws = L.arena_slots + (size_t)c.max_slots * L.slot_bytes;
-  // two copies of the workspace: consecutive backward tasks of the early-backward order run on
-  // two lanes and must not share temporaries (re-computation keeps one lane and one copy)
-  L.ws_copies = L.recompute ? 1 : 2;
+  L.arena_fwd_act = L.arena_slots + (size_t)c.max_slots * L.slot_bytes;
+  L.arena_ws = L.arena_fwd_act + (L.recompute ? align_up(L.act_bytes) : 0);
+  // two copies of the workspace: consecutive backward tasks run on two lanes and must not share
+  // temporaries (a stage without lanes has one backward lane and one copy)
+  L.ws_copies = (c.flags & STAGE_FLAG_ONE_STREAM) ? 1 : 2;
   L.arena_bytes = L.arena_ws + L.ws_copies * L.workspace_bytes;
 }
 
@@ -759,8 +761,10 @@ int stage_init(stage_handle* out, const stage_config* cfg, const void* weights_d
   int rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->grads, h->L.grad_bytes, q); });
   if (rc == STAGE_OK && cfg->has_mlm_head) {
     rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->ws(h->L.wh_info), 16, q); });
-    if (rc == STAGE_OK && h->L.recompute)
-      rc = h->run(KC_COPY, 0, [&](hipStream_t q) { return launch_zero(h->ws(h->L.wh_info2), 16, q); });
+    for (int c = 0; rc == STAGE_OK && h->L.recompute && c < h->L.ws_copies; ++c)   // one flag per backward lane
+      rc = h->run(KC_COPY, 0, [&](hipStream_t q) {
+        return launch_zero(h->ws((size_t)c * h->L.workspace_bytes + h->L.wh_info2), 16, q);
+      });
   }
   if (rc != STAGE_OK) { delete h; return rc; }
   *out = h;
@@ -816,7 +820,7 @@ int stage_fwd(stage_handle h, int mb, const void* x_dev, void* y_dev, const void
       TRY(h->run(KC_COPY, 0, [&](hipStream_t q) {
         return launch_copy(stash + L.st_aux, aux_dev, (size_t)h->cfg.micro_batch * h->cfg.seq * 4, q);
       }));
-    TRY(h->forward(h->ws(L.ws_act[0]), 0, x_dev, y_dev, aux_dev));
+    TRY(h->forward(h->arena + L.arena_fwd_act, 0, x_dev, y_dev, aux_dev));
   } else {
     TRY(h->forward(h->slot(s), 0, x_dev, y_dev, aux_dev));
   }
@@ -836,7 +840,7 @@ int stage_bwd(stage_handle h, int mb, const void* dy_dev, void* dx_dev) {
   if (h->L.recompute && !h->dry) {
     // re-run the forward from the kept input into the backward tasks' buffer, then go backward
     const Layout& L = h->L;
-    char *stash = h->slot(s), *act = h->ws(L.ws_act[1]);
+    char *stash = h->slot(s), *act = h->ws(L.ws_act);
     TRY(h->forward(act, 1, stash + L.st_x, h->ws(L.ws_ydummy), h->cfg.has_mlm_head ? stash + L.st_aux : nullptr));
     TRY(h->backward(act, dy_dev, dx_dev));
   } else {
@@ -1069,7 +1073,8 @@ int stage_apply_adam(stage_handle h, void* weights_dev, float* master_dev, float
 int stage_stats(stage_handle h, stage_stats_t* out) {
   if (!h || !out) return fail(STAGE_E_NULL, "handle and out must not be NULL");
   out->slot_bytes = h->L.slot_bytes;
-  out->peak_activation_bytes = (uint64_t)h->peak_live * h->L.slot_bytes + (h->L.recompute ? 2 * (uint64_t)h->L.act_bytes : 0);
+  out->peak_activation_bytes = (uint64_t)h->peak_live * h->L.slot_bytes +
+                               (h->L.recompute ? (uint64_t)(1 + h->L.ws_copies) * h->L.act_bytes : 0);
   out->live_slots = h->live;
   out->peak_live_slots = h->peak_live;
   out->fwd_tasks = h->fwd_tasks;
@@ -1143,8 +1148,9 @@ int stage_sync(stage_handle h) {
     int32_t info[2] = {0, 0};
     if (hipMemcpy(info, h->ws(h->L.wh_info), 8, hipMemcpyDeviceToHost) != hipSuccess)
       return fail(STAGE_E_DEVICE, "hipMemcpy failed");
-    if (h->L.recompute && !info[1] && hipMemcpy(info, h->ws(h->L.wh_info2), 8, hipMemcpyDeviceToHost) != hipSuccess)
-      return fail(STAGE_E_DEVICE, "hipMemcpy failed");
+    for (int c = 0; h->L.recompute && !info[1] && c < h->L.ws_copies; ++c)
+      if (hipMemcpy(info, h->ws((size_t)c * h->L.workspace_bytes + h->L.wh_info2), 8, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(STAGE_E_DEVICE, "hipMemcpy failed");
     if (info[1]) return fail(STAGE_E_CONFIG, "a micro-batch predicted more rows than mlm_max_rows; the surplus was dropped");
   }
   return STAGE_OK;

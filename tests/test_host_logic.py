@@ -65,15 +65,19 @@ def test_config_errors():
 
 
 def test_recompute_keeps_only_the_boundary_per_slot():
-    # section VI-E: with re-computation a resident micro-batch keeps its input only; the two
-    # activation buffers (forward tasks, backward tasks) do not scale with the slots
+    # section VI-E: with re-computation a resident micro-batch keeps its input only; the activation
+    # buffers (one for the forward tasks, one per backward lane) do not scale with the slots
     full = B.stage_query_sizes(dry(2))
     rc2 = B.stage_query_sizes(dry(2, flags=B.FLAG_DRY_RUN | B.FLAG_RECOMPUTE))
     rc8 = B.stage_query_sizes(dry(8, flags=B.FLAG_DRY_RUN | B.FLAG_RECOMPUTE))
     T, H = 2 * 16, 64
     assert rc2.slot_bytes == T * H * 4 < full.slot_bytes
     assert rc8.arena_bytes - rc2.arena_bytes == 6 * rc2.slot_bytes
-    assert rc2.workspace_bytes >= full.workspace_bytes + 2 * full.slot_bytes
+    assert rc2.workspace_bytes >= full.workspace_bytes + full.slot_bytes          # a backward lane's buffer
+    grads_and_slots = lambda q, k: q.grad_bytes + k * q.slot_bytes
+    assert rc2.arena_bytes - grads_and_slots(rc2, 2) >= 2 * rc2.workspace_bytes + full.slot_bytes   # + the forward tasks' buffer
+    one = B.stage_query_sizes(dry(2, flags=B.FLAG_DRY_RUN | B.FLAG_RECOMPUTE | B.FLAG_ONE_STREAM))
+    assert one.arena_bytes - grads_and_slots(one, 2) < rc2.arena_bytes - grads_and_slots(rc2, 2) - full.slot_bytes
     # first stage: token ids; last stage: input and targets
     emb = B.stage_query_sizes(dry(2, flags=B.FLAG_DRY_RUN | B.FLAG_RECOMPUTE, has_embedding=1, vocab=100, max_pos=16))
     assert emb.slot_bytes == 256          # T int32 ids, rounded up to the 256-byte granule
