@@ -20,22 +20,41 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ G, float*
     // c1 = 1 / (1 - beta1^step), c2 = 1 / (1 - beta2^step)
     wv -= lr * (mv * c1) / (sqrtf(vv * c2) + eps);
   };
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-    float4 g = ((const float4*)G)[i], wv = ((const float4*)w32)[i], mv = ((const float4*)m)[i], vv = ((const float4*)v)[i];
-    upd(g.x, wv.x, mv.x, vv.x);
-    upd(g.y, wv.y, mv.y, vv.y);
-    upd(g.z, wv.z, mv.z, vv.z);
-    upd(g.w, wv.w, mv.w, vv.w);
-    ((float4*)w32)[i] = wv;
-    ((float4*)m)[i] = mv;
-    ((float4*)v)[i] = vv;
+  // Streaming data, touched once per call: non-temporal loads and stores keep it from displacing what the
+  // caches hold; a lane that has more than one vector to do (grids beyond the cap) takes four per turn,
+  // sixteen 16-byte loads in flight before the first store.
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  typedef T T4 __attribute__((ext_vector_type(4)));
+  auto ld = [](const float* p, size_t i) { return __builtin_nontemporal_load((const f4*)p + i); };
+  auto st = [](float* p, size_t i, f4 x) { __builtin_nontemporal_store(x, (f4*)p + i); };
+  auto one = [&](size_t i, f4 g, f4 wv, f4 mv, f4 vv) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float we = wv[e], me = mv[e], ve = vv[e];
+      upd(g[e], we, me, ve);
+      wv[e] = we; mv[e] = me; vv[e] = ve;
+    }
+    st(w32, i, wv);
+    st(m, i, mv);
+    st(v, i, vv);
     // the four weights of the stage's dtype leave in one store (w is 16-byte aligned like the fp32 vectors)
-    typedef T T4 __attribute__((ext_vector_type(4)));
     T4 o;
-    o[0] = from_f32<T>(wv.x); o[1] = from_f32<T>(wv.y); o[2] = from_f32<T>(wv.z); o[3] = from_f32<T>(wv.w);
-    *(T4*)(w + 4 * i) = o;
-    if (zero_grads) ((float4*)G)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = from_f32<T>(wv[e]);
+    __builtin_nontemporal_store(o, (T4*)w + i);
+    if (zero_grads) st(G, i, f4{0.f, 0.f, 0.f, 0.f});
+  };
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n4; i += 4 * stride) {
+    f4 g[4], w4[4], m4[4], v4[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      g[u] = ld(G, i + u * stride); w4[u] = ld(w32, i + u * stride); m4[u] = ld(m, i + u * stride); v4[u] = ld(v, i + u * stride);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) one(i + u * stride, g[u], w4[u], m4[u], v4[u]);
   }
+  for (; i < n4; i += stride) one(i, ld(G, i), ld(w32, i), ld(m, i), ld(v, i));
   // the last n % 4 parameters
   for (size_t i = 4 * n4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
     float wv = w32[i], mv = m[i], vv = v[i];
@@ -51,7 +70,8 @@ hipError_t launch_adam(Dtype dt, float* G, float* w32, float* m, float* v, void*
   if (!n) return hipSuccess;
   const size_t n4 = n / 4;
   size_t blocks = (n4 + 255) / 256;
-  if (blocks > 8192) blocks = 8192;
+  // one vector per lane where the grid allows it: measured 5.8 TB/s against 4.9 with 8192 workgroups striding
+  if (blocks > (1u << 20)) blocks = 1u << 20;
   if (blocks < 1) blocks = 1;
   if (dt == DT_BF16)
     hipLaunchKernelGGL(adam_kernel<bf16>, dim3((unsigned)blocks), dim3(256), 0, st, G, w32, m, v, (bf16*)w, n4, n, lr,
