@@ -66,11 +66,21 @@ int pipeline_warmup_depths(int S, int M, int policy, int D, int32_t* K_out) {
 int pipeline_pivot_stage(int S, int M, const double* F, const double* B) {
   if (!F || !B) return set_error(STAGE_E_NULL, "F and B must not be NULL");
   if (S < 1 || M < 1) return set_error(STAGE_E_BAD_ORDER, "S and M must be positive (S=%d, M=%d)", S, M);
+  // Section IV-B-1 in prose: walking from the last stage towards the first, a stage takes the pivot from the
+  // current candidate when its own steady phase, (M-1)(F_s + B_s), outweighs the candidate's steady phase plus the
+  // forward and backward work of the stages strictly between the two.  That work is kept as a running sum (it
+  // grows by one stage per step and starts over when the pivot moves), so every stage costs one comparison.
   int Q = S - 1;
+  double steady_Q = (M - 1) * (F[Q] + B[Q]), between = 0.0;
   for (int s = S - 2; s >= 0; --s) {
-    double between = 0.0;
-    for (int a = s + 1; a < Q; ++a) between += F[a] + B[a];
-    if ((M - 1) * (F[s] + B[s]) > (M - 1) * (F[Q] + B[Q]) + between) Q = s;
+    const double steady_s = (M - 1) * (F[s] + B[s]);
+    if (steady_s > steady_Q + between) {
+      Q = s;
+      steady_Q = steady_s;
+      between = 0.0;
+    } else {
+      between += F[s] + B[s];
+    }
   }
   return Q;
 }

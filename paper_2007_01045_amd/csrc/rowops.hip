@@ -381,13 +381,12 @@ hipError_t launch_ln_fwd(Dtype dt, const void* z, bool z_f32, const void* gamma,
 template <typename T, int N, bool Z32>
 static hipError_t ln_bwd_launch(const void* dy, const void* z, const float* stats, const void* g, void* dz,
                                 float* partial, int nb, int rows, int H, hipStream_t st) {
-  static bool attr = false;
-  if (!attr) {  // up to 96 KiB of LDS for the widest rows
-    hipError_t e = hipFuncSetAttribute((const void*)ln_bwd_kernel<T, N, Z32>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 12 * 64 * Vec<T>::N * N * 4);
-    if (e != hipSuccess) return e;
-    attr = true;
-  }
+  // up to 96 KiB of LDS for the widest rows; set once per instantiation by whichever host thread comes first
+  // (initialisation of a function-local static is thread-safe)
+  static const hipError_t attr_rc = hipFuncSetAttribute((const void*)ln_bwd_kernel<T, N, Z32>,
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                        12 * 64 * Vec<T>::N * N * 4);
+  if (attr_rc != hipSuccess) return attr_rc;
   size_t sh = (size_t)12 * H * sizeof(float);
   hipLaunchKernelGGL((ln_bwd_kernel<T, N, Z32>), dim3(nb), dim3(256), sh, st, (const T*)dy, z, stats, (const T*)g,
                      (T*)dz, partial, rows, H);
