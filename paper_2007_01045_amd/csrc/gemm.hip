@@ -643,9 +643,12 @@ DAPPLE_GEMM_INST(256, 256, 2, 2, 4, 32)
 DAPPLE_GEMM_INST(256, 128, 2, 2, 3, 64)
 DAPPLE_GEMM_INST(128, 128, 2, 2, 2, 64)
 DAPPLE_GEMM_INST(128, 64, 2, 2, 3, 64)
-// with the column sum of B: the weight-gradient layout, the two tile shapes the stage's products take
+// the weight-gradient layout: 128x128 tiles with the deeper ring of 32-wide k-tiles, and the variants with the
+// column sum of B
 template __global__ void gemm_mfma_kernel<128, 128, 2, 2, 2, true, true, 64, true>(GemmArgs, int, int);
 template __global__ void gemm_mfma_kernel<128, 64, 2, 2, 3, true, true, 64, true>(GemmArgs, int, int);
+template __global__ void gemm_mfma_kernel<128, 128, 2, 2, 4, true, true, 32, true>(GemmArgs, int, int);
+template __global__ void gemm_mfma_kernel<128, 128, 2, 2, 4, true, true, 32, false>(GemmArgs, int, int);
 #undef DAPPLE_GEMM_INST
 
 // ------------------------------------------------------------------ host side
@@ -708,30 +711,41 @@ hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;
   if (gemm_uses_mfma(dt, g)) {
     const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
-    if (g.epi & EPI_BSUM) {   // the weight-gradient layout (checked above), 128-row tiles only
-      if (g.tile == 3 || (g.tile != 4 && t128 >= 192)) return launch_mfma<128, 128, 2, 2, 2, true, true, 64, true>(g, st);
-      return launch_mfma<128, 64, 2, 2, 3, true, true, 64, true>(g, st);
-    }
-    // GemmArgs::tile names a configuration (tests, timing); 0 = the choice below
-    switch (g.tile) {
-      case 1: return launch_mfma_layout<256, 256, 2, 2, 4, 32>(g, st);
-      case 2: return launch_mfma_layout<256, 128, 2, 2, 3, 64>(g, st);
-      case 3: return launch_mfma_layout<128, 128, 2, 2, 2, 64>(g, st);
-      case 4: return launch_mfma_layout<128, 64, 2, 2, 3, 64>(g, st);
-      default: break;
-    }
+    const long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
+    const bool tt = g.a_kstrided && g.b_kstrided;   // the weight-gradient layout
+    const bool bsum = (g.epi & EPI_BSUM) != 0;      // (offered for that layout only: checked above)
     // Tile choice.  Every k-tile goes global -> LDS through the compute unit's vector cache at 64 bytes per
     // clock, against 4096 MFMA flops per clock: a 128x128 tile moves one byte per 64 flops (the two rates just
     // balance), a 128x64 tile one per 43, a 256x256 tile one per 128.  So: 256x256 tiles (one workgroup per
     // compute unit, a four-stage ring of 32-wide k-tiles) when they alone fill the chip at least twice;
     // 128x128 tiles (two workgroups per unit) when there are at least 192 of them; else 128x64 tiles with a
     // three-stage ring, so that the small products of a stage (2048 x 1024 outputs) still reach every unit.
-    // Measured inside the stage, with its four streams running, the choice between the last two moves the
-    // iteration by less than 2%: what the products wait for there is that global -> LDS path, not the MFMAs.
-    const long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
-    if (t256 >= 512) return launch_mfma_layout<256, 256, 2, 2, 4, 32>(g, st);
-    if (t128 >= 192) return launch_mfma_layout<128, 128, 2, 2, 2, 64>(g, st);
-    return launch_mfma_layout<128, 64, 2, 2, 3, 64>(g, st);
+    // Weight-gradient products with at least 192 tiles take 128x128 with a four-stage ring of 32-wide k-tiles
+    // in the same 64 KB of LDS: both operands are k-strided there, so a 32-deep k-tile still reads whole
+    // 256-byte rows, and three tiles in flight instead of one hide the latency a two-stage ring waits for at
+    // every k-tile (1024 x 4096 x 2048 in place: 43 -> 33 us).  Measured inside the stage, with its four streams
+    // running, the choice among the 128-row tiles moves the iteration by less than 2%: what the products wait
+    // for there is the global -> LDS path, not the MFMAs.
+    // GemmArgs::tile names a configuration instead (tests, timing).  Tile 5 and the column sums of B exist for
+    // the weight-gradient layout only, the latter with 128-row tiles only.
+    int tile = g.tile;
+    if (tile == 5 && !tt) tile = 3;
+    if (bsum && (tile == 1 || tile == 2)) tile = 0;
+    if (tile == 0) {
+      if (tt && t128 >= 192) tile = 5;
+      else if (t256 >= 512 && !bsum) tile = 1;
+      else tile = t128 >= 192 ? 3 : 4;
+    }
+    switch (tile) {
+      case 1: return launch_mfma_layout<256, 256, 2, 2, 4, 32>(g, st);
+      case 2: return launch_mfma_layout<256, 128, 2, 2, 3, 64>(g, st);
+      case 3: return bsum ? launch_mfma<128, 128, 2, 2, 2, true, true, 64, true>(g, st)
+                          : launch_mfma_layout<128, 128, 2, 2, 2, 64>(g, st);
+      case 5: return bsum ? launch_mfma<128, 128, 2, 2, 4, true, true, 32, true>(g, st)
+                          : launch_mfma<128, 128, 2, 2, 4, true, true, 32, false>(g, st);
+      default: return bsum ? launch_mfma<128, 64, 2, 2, 3, true, true, 64, true>(g, st)
+                           : launch_mfma_layout<128, 64, 2, 2, 3, 64>(g, st);
+    }
   }
   dim3 blk(32, 8);
   dim3 grid((g.N + 31) / 32, (g.M + 7) / 8, g.batch);
