@@ -88,8 +88,11 @@ struct Layout {
   size_t act_bytes = 0, st_x = 0, st_aux = 0, ws_act = 0, ws_ydummy = 0, arena_fwd_act = 0;
   // workspace (bytes)
   // buffers the side stream reads exist twice (layers alternate between the sets)
-  size_t ws_dx[2] = {0, 0}, ws_dz2[2] = {0, 0}, ws_du[2] = {0, 0}, ws_dy1 = 0, ws_dz1[2] = {0, 0}, ws_dctx = 0,
-         ws_dqkv[2] = {0, 0}, ws_delta = 0, ws_part_ln2[2] = {0, 0}, ws_part_ln1[2] = {0, 0}, ws_head = 0;
+  size_t ws_dx[2] = {0, 0}, ws_dy1 = 0, ws_dctx = 0, ws_delta = 0, ws_head = 0;
+  // what the side stream reads of a layer's backward (one set per layer: the backward chain of a task never
+  // waits for the side stream before its end)
+  struct SideSet { size_t dz2, du, dz1, dqkv, part_ln2, part_ln1; };
+  std::vector<SideSet> ws_side;
   size_t workspace_bytes = 0;
   // arena
   size_t grad_bytes = 0, arena_grads = 0, arena_slots = 0, arena_ws = 0, arena_bytes = 0;
@@ -184,10 +187,11 @@ void build_layout(const stage_config& c, Layout& L) {
       L.ws_y1f[fs] = wtake(T * H * 4); L.ws_yf[fs][0] = wtake(T * H * 4); L.ws_yf[fs][1] = wtake(T * H * 4);
     }
   }
-  const size_t ln_part = ((T + 7) / 8) * 3 * H * 4, cs_rows = (T + 63) / 64;
-  for (int p = 0; p < 2; ++p) {
-    L.ws_dz2[p] = wtake(U); L.ws_du[p] = wtake(T * F * E); L.ws_dz1[p] = wtake(U); L.ws_dqkv[p] = wtake(3 * U);
-    L.ws_part_ln2[p] = wtake(ln_part); L.ws_part_ln1[p] = wtake(ln_part);
+  const size_t ln_part = ((T + 7) / 8) * 3 * H * 4;
+  L.ws_side.resize(c.n_layers);
+  for (auto& ss : L.ws_side) {
+    ss.dz2 = wtake(U); ss.du = wtake(T * F * E); ss.dz1 = wtake(U); ss.dqkv = wtake(3 * U);
+    ss.part_ln2 = wtake(ln_part); ss.part_ln1 = wtake(ln_part);
   }
   if (c.has_mlm_head) {
     const size_t NP = L.NP, VP = L.VP;
@@ -501,9 +505,9 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
   for (int l = cfg.n_layers - 1; l >= 0; --l) {
     const LayerParams& p = L.lp[l];
     const LayerStash& a = L.ls[l];
-    const int ps = l & 1;  // workspace set of this layer
-    char *dz2 = ws(L.ws_dz2[ps]), *du = ws(L.ws_du[ps]), *dz1 = ws(L.ws_dz1[ps]), *dqkv = ws(L.ws_dqkv[ps]);
-    float *part_ln2 = (float*)ws(L.ws_part_ln2[ps]), *part_ln1 = (float*)ws(L.ws_part_ln1[ps]);
+    const Layout::SideSet& ss = L.ws_side[l];  // this layer's buffers that the side stream reads
+    char *dz2 = ws(ss.dz2), *du = ws(ss.du), *dz1 = ws(ss.dz1), *dqkv = ws(ss.dqkv);
+    float *part_ln2 = (float*)ws(ss.part_ln2), *part_ln1 = (float*)ws(ss.part_ln1);
     const char* xl = l == 0 ? sl + L.slot_x0 : sl + L.ls[l - 1].y;
     char *qkv = sl + a.qkv, *ctx = sl + a.ctx, *z1 = sl + a.z1, *y1 = sl + a.y1, *gp = sl + a.gp, *g = sl + a.g,
          *z2 = sl + a.z2;
@@ -511,8 +515,6 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     char* dxout = l == 0 ? (cfg.has_embedding ? ws(L.we_dx0) : (char*)dx) : ws(L.ws_dx[l & 1]);
     const size_t pstride = (size_t)H * H + H;
     int nblk = 0;
-    // this layer's workspace set was last read by the side work of layer l + 2
-    if (l + 2 < cfg.n_layers) TRY(join(l + 2));
 
     // y = LN(z2): dz2, and block partial sums for the gradients of ln2 gain/shift and of b2
     TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dyin, z2, dt == DT_BF16, st2, w(p.ln2g), dz2, part_ln2, &nblk, T, H, q); }));
@@ -622,9 +624,8 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
   }
   // The task ends when both streams are done: whatever follows on the caller's stream (the next
   // forward reusing this slot, a gradient read-out) is ordered after the accumulator updates.
+  // (the side stream is in order and layer 0's work is the last it was given)
   TRY(join(0));
-  if (cfg.n_layers > 1) TRY(join(1));
-  if (cfg.has_mlm_head) TRY(join(cfg.n_layers));
   return STAGE_OK;
 }
 
