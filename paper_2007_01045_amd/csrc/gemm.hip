@@ -487,8 +487,63 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   } else {
     main_loop(std::false_type{});
   }
+  if constexpr (CS) {
+    // every row of csum holds the column sums: the lanes of row 0 add them to bsum (one workgroup per column
+    // range does, so the add needs no atomic)
+    if (do_cs && (lane & 31) == 0) {
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int col = n0 + wn0 + 32 * j + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (col < g.N) bsum_ptr[col] += csum[j][v];
+        }
+    }
+  }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // the tail requests (they read nothing) must be done before LDS is reused
-  __syncthreads();  // every wave has read its last fragments: LDS can be reused
+  // The residual / gate operand of the epilogue is requested HERE, before the workgroup's last barrier and the
+  // staging of the accumulators through LDS, so that its latency (up to a few microseconds when it comes from
+  // HBM) passes behind them instead of being waited for once per 32-row block.  Only for the 128-row tiles: larger
+  // ones would need more registers than the accumulators leave.  (The fp32 C of an accumulating product is NOT
+  // requested early: measured, that costs 3 us per launch more than it hides, like every other early read of C.)
+  const long zc = g.Cz[0] ? 0 : z * g.sC, zbias = z * g.sBias;
+  constexpr int C4 = CFG::WN / 4;             // float4 per staged row
+  constexpr int NIT = 32 * C4 / 64;           // float4 per lane per 32-row block
+  constexpr int HB = NIT > 8 ? 8 : NIT;       // processed HB at a time
+  constexpr bool PRE = MI * NIT <= 16;
+  const int epi = g.epi;
+  // (native vectors: arrays of the runtime's float4, a struct around a union, stay in scratch memory; a bf16
+  // operand's four values sit in the first two lanes)
+  f32x4 pre[PRE ? MI : 1][PRE ? NIT : 1];
+  if constexpr (PRE) {
+    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N;
+    if (epi & (EPI_ADD | EPI_MUL)) {
+      const int ldp = g.ldaux;
+      const bool p32 = (epi & EPI_AUX32) != 0;
+      const void* base = g.aux;
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int n = 0; n < NIT; ++n) {
+          const int idx = n * 64 + lane, r = idx / C4, c4 = idx % C4;
+          const int row = m0 + wm0 + i * 32 + r, col = n0 + wn0 + c4 * 4;
+          const bool ok = interior || (row < g.M && col < g.N);
+          const long o = ok ? zc + (long)row * ldp + col : zc;
+          if (p32) {
+            pre[i][n] = *(const f32x4*)((const float*)base + o);
+          } else {
+            typedef float f32x2 __attribute__((__vector_size__(2 * sizeof(float))));
+            const f32x2 h2 = *(const f32x2*)((const bf16*)base + o);
+            pre[i][n] = f32x4{h2[0], h2[1], 0.f, 0.f};
+          }
+        }
+    }
+  }
+  // every wave has read its last fragments (lgkmcnt(0)): LDS can be reused after the barrier.  The raw barrier on
+  // purpose: __syncthreads() would also wait for the requests just issued.
+  __builtin_amdgcn_s_waitcnt(0xC07F);
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
   // epilogue: per wave, 32 output rows at a time through an fp32 LDS staging tile that
   // turns "a lane owns 4 columns of one row" into row-contiguous stores.
@@ -496,11 +551,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   // All LDS reads (and aux / C reads) of a half block are issued before the first use,
   // so their latencies overlap instead of adding up.
   float* stg = (float*)smem + wave * 32 * CFG::EPI_LD;
-  const long zc = g.Cz[0] ? 0 : z * g.sC, zbias = z * g.sBias;
-  constexpr int C4 = CFG::WN / 4;             // float4 per staged row
-  constexpr int NIT = 32 * C4 / 64;           // float4 per lane per 32-row block
-  constexpr int HB = NIT > 8 ? 8 : NIT;       // processed HB at a time
-  const int epi = g.epi;
   // one 32-row block; the block index is a compile-time constant so that the
   // accumulators are always addressed statically (they must stay in registers)
   auto store_block = [&](auto I, auto FULLC) {
@@ -542,13 +592,24 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
           float4 xv[HB];
 #pragma unroll
           for (int u = 0; u < HB; ++u) {
-            bool ok = FULL || (rows[u] < g.M && cols[u] < g.N);
-            long o = ok ? zc + (long)rows[u] * g.ldaux + cols[u] : zc;
-            if (epi & EPI_AUX32) {
-              xv[u] = *(const float4*)((const float*)g.aux + o);
+            if constexpr (PRE) {
+              const f32x4 pv = pre[i][hb + u];
+              if (epi & EPI_AUX32) {
+                xv[u] = make_float4(pv[0], pv[1], pv[2], pv[3]);
+              } else {
+                typedef float f32x2 __attribute__((__vector_size__(2 * sizeof(float))));
+                const bf16x4 b4 = __builtin_bit_cast(bf16x4, f32x2{pv[0], pv[1]});
+                xv[u] = make_float4((float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]);
+              }
             } else {
-              bf16x4 b4 = *(const bf16x4*)((const bf16*)g.aux + o);
-              xv[u] = make_float4((float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]);
+              bool ok = FULL || (rows[u] < g.M && cols[u] < g.N);
+              long o = ok ? zc + (long)rows[u] * g.ldaux + cols[u] : zc;
+              if (epi & EPI_AUX32) {
+                xv[u] = *(const float4*)((const float*)g.aux + o);
+              } else {
+                bf16x4 b4 = *(const bf16x4*)((const bf16*)g.aux + o);
+                xv[u] = make_float4((float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]);
+              }
             }
           }
 #pragma unroll
@@ -618,19 +679,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   if (m0 + BM <= g.M && n0 + BN <= g.N) store_tile(std::true_type{});
   else store_tile(std::false_type{});
   static_assert(MI <= 4, "at most four 32-row blocks per wave");
-  if constexpr (CS) {
-    // every row of csum holds the column sums: the lanes of row 0 add them to bsum (one workgroup per column
-    // range does, so the add needs no atomic)
-    if (do_cs && (lane & 31) == 0) {
-#pragma unroll
-      for (int j = 0; j < NI; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int col = n0 + wn0 + 32 * j + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          if (col < g.N) bsum_ptr[col] += csum[j][v];
-        }
-    }
-  }
 }
 
 // explicit instantiations (every tile shape x operand layout the launcher can pick)
