@@ -197,8 +197,8 @@ def algorithmic_bytes(cls, cfg):
     u = T * H
     if cls == "ln_fwd":     # reads the fp32 pre-LN sum, writes y (and its fp32 copy for the next residual add) + stats
         return u * (4 + e + 4) + 8 * T if cfg.dtype == "bf16" else u * 8 + 8 * T
-    if cls == "ln_bwd":     # reads dy and the pre-LN sum, writes dz and the per-block partial sums
-        return u * (e + 4 + e) + (T // 32) * 3 * H * 4 if cfg.dtype == "bf16" else u * 12
+    if cls == "ln_bwd":     # reads dy and the pre-LN sum, writes dz and one partial-sum triple per block of 8 rows
+        return u * (e + 4 + e) + ((T + 7) // 8) * 3 * H * 4 if cfg.dtype == "bf16" else u * 12 + ((T + 7) // 8) * 3 * H * 4
     return None
 
 

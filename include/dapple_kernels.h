@@ -57,7 +57,7 @@ typedef struct {
   int32_t tile;   /* 0 = automatic; else one configuration of the MFMA kernel, for tests and timing:
                    * 1: 256x256 tile, four-stage ring of 32-wide k-tiles; 2: 256x128, three stages of 64;
                    * 3: 128x128, two stages of 64; 4: 128x64, three stages of 64; 5: 128x128, four stages of 32
-                   * (both operands k-strided; any other layout gets 3) */
+                   * (both operands k-strided; any other layout gets 3); 6: 256x128, three stages of 32 */
 } dapple_gemm_desc;
 
 /* Returns 1 if the bf16 MFMA kernel takes this problem, 0 if the plain kernel does. */

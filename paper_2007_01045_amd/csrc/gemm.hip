@@ -510,33 +510,36 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
   constexpr int C4 = CFG::WN / 4;             // float4 per staged row
   constexpr int NIT = 32 * C4 / 64;           // float4 per lane per 32-row block
   constexpr int HB = NIT > 8 ? 8 : NIT;       // processed HB at a time
-  constexpr bool PRE = MI * NIT <= 16;
+  constexpr bool PRE = !CS && MI * NIT <= 16;   // (the column-sum variant serves accumulating products only)
   const int epi = g.epi;
   // (native vectors: arrays of the runtime's float4, a struct around a union, stay in scratch memory; a bf16
   // operand's four values sit in the first two lanes)
   f32x4 pre[PRE ? MI : 1][PRE ? NIT : 1];
-  if constexpr (PRE) {
+  // one 32-row block of that operand, as each lane will use it in store_block
+  auto load_aux_block = [&](int i, f32x4 (&dst)[NIT]) {
     const bool interior = m0 + BM <= g.M && n0 + BN <= g.N;
+    const int ldp = g.ldaux;
+    const bool p32 = (epi & EPI_AUX32) != 0;
+    const void* base = g.aux;
+#pragma unroll
+    for (int n = 0; n < NIT; ++n) {
+      const int idx = n * 64 + lane, r = idx / C4, c4 = idx % C4;
+      const int row = m0 + wm0 + i * 32 + r, col = n0 + wn0 + c4 * 4;
+      const bool ok = interior || (row < g.M && col < g.N);
+      const long o = ok ? zc + (long)row * ldp + col : zc;
+      if (p32) {
+        dst[n] = *(const f32x4*)((const float*)base + o);
+      } else {
+        typedef float f32x2 __attribute__((__vector_size__(2 * sizeof(float))));
+        const f32x2 h2 = *(const f32x2*)((const bf16*)base + o);
+        dst[n] = f32x4{h2[0], h2[1], 0.f, 0.f};
+      }
+    }
+  };
+  if constexpr (PRE) {
     if (epi & (EPI_ADD | EPI_MUL)) {
-      const int ldp = g.ldaux;
-      const bool p32 = (epi & EPI_AUX32) != 0;
-      const void* base = g.aux;
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int n = 0; n < NIT; ++n) {
-          const int idx = n * 64 + lane, r = idx / C4, c4 = idx % C4;
-          const int row = m0 + wm0 + i * 32 + r, col = n0 + wn0 + c4 * 4;
-          const bool ok = interior || (row < g.M && col < g.N);
-          const long o = ok ? zc + (long)row * ldp + col : zc;
-          if (p32) {
-            pre[i][n] = *(const f32x4*)((const float*)base + o);
-          } else {
-            typedef float f32x2 __attribute__((__vector_size__(2 * sizeof(float))));
-            const f32x2 h2 = *(const f32x2*)((const bf16*)base + o);
-            pre[i][n] = f32x4{h2[0], h2[1], 0.f, 0.f};
-          }
-        }
+      for (int i = 0; i < MI; ++i) load_aux_block(i, pre[i]);
     }
   }
   // every wave has read its last fragments (lgkmcnt(0)): LDS can be reused after the barrier.  The raw barrier on
@@ -691,6 +694,7 @@ DAPPLE_GEMM_INST(256, 256, 2, 2, 4, 32)
 DAPPLE_GEMM_INST(256, 128, 2, 2, 3, 64)
 DAPPLE_GEMM_INST(128, 128, 2, 2, 2, 64)
 DAPPLE_GEMM_INST(128, 64, 2, 2, 3, 64)
+DAPPLE_GEMM_INST(256, 128, 2, 2, 3, 32)
 // the weight-gradient layout: 128x128 tiles with the deeper ring of 32-wide k-tiles, and the variants with the
 // column sum of B
 template __global__ void gemm_mfma_kernel<128, 128, 2, 2, 2, true, true, 64, true>(GemmArgs, int, int);
@@ -763,24 +767,34 @@ hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st) {
     const bool tt = g.a_kstrided && g.b_kstrided;   // the weight-gradient layout
     const bool bsum = (g.epi & EPI_BSUM) != 0;      // (offered for that layout only: checked above)
     // Tile choice.  Every k-tile goes global -> LDS through the compute unit's vector cache at 64 bytes per
-    // clock, against 4096 MFMA flops per clock: a 128x128 tile moves one byte per 64 flops (the two rates just
-    // balance), a 128x64 tile one per 43, a 256x256 tile one per 128.  So: 256x256 tiles (one workgroup per
-    // compute unit, a four-stage ring of 32-wide k-tiles) when they alone fill the chip at least twice;
-    // 128x128 tiles (two workgroups per unit) when there are at least 192 of them; else 128x64 tiles with a
-    // three-stage ring, so that the small products of a stage (2048 x 1024 outputs) still reach every unit.
+    // clock, and from LDS to the waves at 128 bytes per clock, against 4096 MFMA flops per clock.  A 128x128
+    // tile (64x64 per wave) needs the vector cache's whole rate and 1.5 times what LDS can do (fragment reads
+    // plus the arriving tiles) to keep the matrix cores busy; a 256x128 tile (128x64 per wave) 0.75 of the one
+    // and 1.1 of the other; a 256x256 tile half of each, but it takes a whole compute unit.  So:
+    //  - 256x256 tiles (one workgroup per unit, a four-stage ring of 32-wide k-tiles) when they alone fill the
+    //    chip at least twice;
+    //  - 256x128 tiles with a three-stage ring of 32-wide k-tiles (72 KB of LDS, 240 registers: two workgroups
+    //    fit a unit, or one next to a workgroup of another stream's kernel) for products of at least 384
+    //    128x128 tiles whose operands are not both k-strided and whose epilogue reads no second operand (this
+    //    tile has no registers left to request it early).  Alone such a product is no faster than with
+    //    128x128 tiles (2048 x 4096 x 1024: 23.6 against 22.4 us, one workgroup per unit); inside the stage,
+    //    where the units are shared with the other streams' kernels, the iteration gains 2%.  A deeper ring
+    //    (96 KB) loses more than that: the workgroup no longer fits beside another kernel's;
+    //  - 128x128 tiles (two workgroups per unit) when there are at least 192 of them;
+    //  - else 128x64 tiles with a three-stage ring, so that the small products of a stage (2048 x 1024 outputs)
+    //    still reach every unit.
     // Weight-gradient products with at least 192 tiles take 128x128 with a four-stage ring of 32-wide k-tiles
     // in the same 64 KB of LDS: both operands are k-strided there, so a 32-deep k-tile still reads whole
     // 256-byte rows, and three tiles in flight instead of one hide the latency a two-stage ring waits for at
-    // every k-tile (1024 x 4096 x 2048 in place: 43 -> 33 us).  Measured inside the stage, with its four streams
-    // running, the choice among the 128-row tiles moves the iteration by less than 2%: what the products wait
-    // for there is the global -> LDS path, not the MFMAs.
+    // every k-tile (1024 x 4096 x 2048 in place: 43 -> 33 us).
     // GemmArgs::tile names a configuration instead (tests, timing).  Tile 5 and the column sums of B exist for
     // the weight-gradient layout only, the latter with 128-row tiles only.
     int tile = g.tile;
     if (tile == 5 && !tt) tile = 3;
-    if (bsum && (tile == 1 || tile == 2)) tile = 0;
+    if (bsum && (tile == 1 || tile == 2 || tile == 6)) tile = 0;
     if (tile == 0) {
       if (tt && t128 >= 192) tile = 5;
+      else if (!tt && t128 >= 384 && t256 < 512 && !(g.epi & (EPI_ADD | EPI_MUL))) tile = 6;
       else if (t256 >= 512 && !bsum) tile = 1;
       else tile = t128 >= 192 ? 3 : 4;
     }
@@ -789,6 +803,7 @@ hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st) {
       case 2: return launch_mfma_layout<256, 128, 2, 2, 3, 64>(g, st);
       case 3: return bsum ? launch_mfma<128, 128, 2, 2, 2, true, true, 64, true>(g, st)
                           : launch_mfma_layout<128, 128, 2, 2, 2, 64>(g, st);
+      case 6: return launch_mfma_layout<256, 128, 2, 2, 3, 32>(g, st);
       case 5: return bsum ? launch_mfma<128, 128, 2, 2, 4, true, true, 32, true>(g, st)
                           : launch_mfma<128, 128, 2, 2, 4, true, true, 32, false>(g, st);
       default: return bsum ? launch_mfma<128, 64, 2, 2, 3, true, true, 64, true>(g, st)

@@ -52,7 +52,7 @@ struct GemmArgs {
   int k_valid;  // k-strided operands: rows k >= k_valid read as zero (K itself is padded)
   int m_valid, n_valid;  // rows of A / B that exist in memory (0 = M / N); rows beyond read as zero
   int epi;
-  int tile;  // 0 = automatic choice; 1..5 = a specific tile shape / ring depth (see launch_gemm)
+  int tile;  // 0 = automatic choice; 1..6 = a specific tile shape / ring depth (see launch_gemm)
 };
 
 hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st);

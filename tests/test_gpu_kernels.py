@@ -88,7 +88,7 @@ def gemm_case(dtype, M, N, K, akS, bkS, epi, batch=1, nseg=1, expect_mfma=None, 
         assert np.abs(g - w).max() < (3e-2 if bf else 1e-4) * max(np.abs(w).max(), 1.0)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
 def test_gemm_mfma_every_tile_shape_and_ring_depth(tile):
     # K = 64 * (1, 2, 3, 5, 7, 8): shorter than the ring, a multiple of no ring depth, and longer;
     # ragged M and N; both operand layouts; a segmented K
@@ -250,7 +250,7 @@ def test_gemm_random_shapes(seed):
         akS, bkS = rng.random() < 0.5, rng.random() < 0.5
         epi = rng.choice(epis)
         batch = rng.choice([1, 1, 2, 3])
-        tile = rng.randint(0, 5)
+        tile = rng.randint(0, 6)
         print(f"case {case}: dtype={dtype} M={M} N={N} K={K} akS={akS} bkS={bkS} epi={epi} batch={batch} nseg={nseg} "
               f"tile={tile}", flush=True)
         gemm_case(dtype, M, N, K, akS, bkS, epi, batch=batch, nseg=nseg, tile=tile)
