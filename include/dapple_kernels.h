@@ -26,8 +26,16 @@ enum {
   DAPPLE_EPI_GELU = 8,  /* C = GELU(t), C2 = GELU'(t) */
   DAPPLE_EPI_ACC32 = 16, /* C is fp32 and C += t  (weight-gradient accumulation over
                             micro-batches, section V-B-3 of the DAPPLE paper) */
-  DAPPLE_EPI_BSUM = 128  /* bsum[n] += sum_k B(n,k): the bias gradient (column sums of the output gradient)
+  DAPPLE_EPI_OUT32 = 32, /* C is fp32 and C = t */
+  DAPPLE_EPI_AUX32 = 64, /* aux is fp32 although the product is bf16 (the unrounded residual stream) */
+  DAPPLE_EPI_BSUM = 128, /* bsum[n] += sum_k B(n,k): the bias gradient (column sums of the output gradient)
                             in the launch of the weight gradient; both operands k-strided, batch 1 */
+  DAPPLE_EPI_ROWDOT = 256 /* rowdot[j*M + m] = sum over the columns n in [32j, 32j+32) of C[m,n] (as stored,
+                            rounded to bf16) * aux[m,n]; aux is neither added nor multiplied in.  The stage
+                            backward B_s uses it on the product that makes the attention output's gradient:
+                            the row sums rowsum(dctx o ctx) per head that the softmax backward needs are then
+                            two of these blocks.  bf16 MFMA path only (anything else: STAGE_E_CONFIG), no other
+                            epilogue than BIAS and AUX32 beside it, batch 1 */
 };
 
 /* C[m,n] = epilogue(sum_k A(m,k) B(n,k)).  A k-contiguous operand is X(r,k) =
@@ -45,6 +53,7 @@ typedef struct {
   const void* bias;
   const void* aux;
   float* bsum;    /* DAPPLE_EPI_BSUM: fp32 [N], accumulated into */
+  float* rowdot;  /* DAPPLE_EPI_ROWDOT: fp32 [ceil(N/32)][M], overwritten */
   int32_t M, N, K;
   int32_t lda, ldb, ldc, ldaux;
   int32_t a_kstrided, b_kstrided;

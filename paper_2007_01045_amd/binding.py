@@ -23,6 +23,7 @@ FLAG_DRY_RUN = 1
 FLAG_RECOMPUTE = 2
 FLAG_ONE_STREAM = 4
 EPI_BIAS, EPI_ADD, EPI_MUL, EPI_GELU, EPI_ACC32, EPI_BSUM = 1, 2, 4, 8, 16, 128
+EPI_OUT32, EPI_AUX32, EPI_ROWDOT = 32, 64, 256
 
 
 class stage_config(C.Structure):
@@ -45,7 +46,7 @@ class stage_stats_t(C.Structure):
 
 class dapple_gemm_desc(C.Structure):
     _fields_ = [("A", C.c_void_p), ("B", C.c_void_p), ("C", C.c_void_p), ("C2", C.c_void_p),
-                ("bias", C.c_void_p), ("aux", C.c_void_p), ("bsum", C.c_void_p),
+                ("bias", C.c_void_p), ("aux", C.c_void_p), ("bsum", C.c_void_p), ("rowdot", C.c_void_p),
                 ("M", C.c_int32), ("N", C.c_int32), ("K", C.c_int32),
                 ("lda", C.c_int32), ("ldb", C.c_int32), ("ldc", C.c_int32), ("ldaux", C.c_int32),
                 ("a_kstrided", C.c_int32), ("b_kstrided", C.c_int32), ("kseg_len", C.c_int32),

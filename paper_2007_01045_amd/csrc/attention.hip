@@ -13,9 +13,16 @@
 // owns: softmax statistics are then per-lane scalars, and the probabilities leave
 // the accumulator already laid out as the next MFMA's operand (the contraction
 // index is permuted, and the other operand is fetched from LDS with the same
-// permutation through the LDS transpose read).  dq and dk/dv are two kernels that
-// each recompute P: no atomics, every sum in a fixed order, so results are
-// reproducible bit for bit.
+// permutation through the LDS transpose read).  dq and dk/dv are two sets of
+// workgroups that each recompute P: no atomics, every sum in a fixed order, so
+// results are reproducible bit for bit.  Both sets go out in ONE launch (grid.z
+// picks the role) with at most 256 registers per lane, so that a dq and a dk/dv
+// workgroup share a compute unit: each is a chain MFMA -> softmax arithmetic ->
+// MFMA with one wave per SIMD, and two of them on a SIMD fill each other's waits
+// (b=4, s=512, A=16: 39 us as two launches one after the other, 29 us as one).
+// delta = rowsum(dctx o ctx) must exist before either starts: the stage takes it
+// from the epilogue of the product that makes dctx (delta_blocks), a caller
+// without that product gets it from a small kernel of its own first.
 //
 // Plain kernels (any dtype and shape): one thread per output element, used by the
 // fp32 configuration and by shapes the MFMA kernels do not take.
@@ -181,6 +188,16 @@ __device__ __forceinline__ bf16x8 acc_to_operand(const float (&p)[16], int ks) {
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
+// delta of query row qi of sequence bi, head hh: from [b, A, s], or the head's two blocks of 32 columns
+// out of [H/32][b*s]
+__device__ __forceinline__ float delta_at(const AttnArgs& a, int bi, int hh, int qi) {
+  if (a.delta_blocks) {
+    const long T = (long)a.b * a.s, row = (long)bi * a.s + qi;
+    return a.delta_blocks[(2 * hh) * T + row] + a.delta_blocks[(2 * hh + 1) * T + row];
+  }
+  return a.delta[((long)bi * a.A + hh) * a.s + qi];
+}
+
 // 2^x for x <= 0 as the bare v_exp_f32: the library exp2f wraps it in three more instructions that
 // rescale denormal results, and a probability below 2^-126 may as well be zero
 __device__ __forceinline__ float exp2_neg(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -300,7 +317,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnArgs a, float scale2) {
 }
 
 // dk, dv: the wave owns 32 key rows; query blocks of 64 stream through LDS
-__global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, float scale) {
+__device__ __forceinline__ void attn_dkdv_body(const AttnArgs& a, float scale2, float scale) {
   __shared__ __attribute__((aligned(16))) bf16 Qs[64 * AD];
   __shared__ __attribute__((aligned(16))) bf16 Gs[64 * AD];
   __shared__ __attribute__((aligned(16))) float Ls[64];
@@ -311,7 +328,6 @@ __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, 
   const bf16 *Q = (const bf16*)a.q + hb, *K = (const bf16*)a.k + hb, *V = (const bf16*)a.v + hb,
              *G = (const bf16*)a.dctx + hb;
   const float* lse = a.lse + ((long)bi * a.A + hh) * a.s;
-  const float* dl = a.delta + ((long)bi * a.A + hh) * a.s;
   const int krow = blockIdx.x * 128 + wave * 32 + (lane & 31);
   const bool kok = krow < a.s;
 
@@ -326,7 +342,7 @@ __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, 
   Block64 qblk, gblk;  // the next query / dctx block, in flight while the current one is used
   qblk.load(Q, a.H, tid);
   gblk.load(G, a.H, tid);
-  float stat = tid < 64 ? lse[tid] : (tid < 128 ? dl[tid - 64] : 0.f);
+  float stat = tid < 64 ? lse[tid] : (tid < 128 ? delta_at(a, bi, hh, tid - 64) : 0.f);
 
   for (int qb = 0; qb < nqb; ++qb) {
     __syncthreads();
@@ -339,7 +355,7 @@ __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, 
       const int nb = qb + 1 < nqb ? qb + 1 : qb;
       qblk.load(Q + (long)nb * 64 * a.H, a.H, tid);
       gblk.load(G + (long)nb * 64 * a.H, a.H, tid);
-      stat = tid < 64 ? lse[nb * 64 + tid] : (tid < 128 ? dl[nb * 64 + tid - 64] : 0.f);
+      stat = tid < 64 ? lse[nb * 64 + tid] : (tid < 128 ? delta_at(a, bi, hh, nb * 64 + tid - 64) : 0.f);
     }
 #pragma unroll
     for (int qb2 = 0; qb2 < 2; ++qb2) {
@@ -414,7 +430,7 @@ __global__ __launch_bounds__(256) void attn_dkdv_mfma(AttnArgs a, float scale2, 
 }
 
 // dq: the wave owns 32 query rows; key blocks of 64 stream through LDS
-__global__ __launch_bounds__(256) void attn_dq_mfma(AttnArgs a, float scale2, float scale) {
+__device__ __forceinline__ void attn_dq_body(const AttnArgs& a, float scale2, float scale) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[64 * AD];
   __shared__ __attribute__((aligned(16))) bf16 Vs[64 * AD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
@@ -426,31 +442,13 @@ __global__ __launch_bounds__(256) void attn_dq_mfma(AttnArgs a, float scale2, fl
   const bool qok = qrow < a.s;
   const float Lq = qok ? a.lse[((long)bi * a.A + hh) * a.s + qrow] : 0.f;
 
+  const float Dq = qok ? delta_at(a, bi, hh, qrow) : 0.f;
   bf16x8 qf[4], gf[4];
-  // delta = rowsum(dctx o ctx) of the lane's query row: each half-wave holds 32 of the 64
-  // head columns; the sum is published for the dk/dv kernel, which runs after this one
-  const bf16* O = (const bf16*)a.ctx + hb;
-  float Dq = 0.f;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     qf[kk] = frag_global(Q, qrow, qok, a.H, kk, lane);
     gf[kk] = frag_global(G, qrow, qok, a.H, kk, lane);
-    if (a.ctx32) {
-      if (qok) {
-        const float* o32 = a.ctx32 + hb + (long)qrow * a.H + kk * 16 + 8 * h;
-        float4 lo = *(const float4*)o32, hi = *(const float4*)(o32 + 4);
-        float ov[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) Dq = fmaf((float)gf[kk][e], ov[e], Dq);
-      }
-    } else {
-      bf16x8 of = frag_global(O, qrow, qok, a.H, kk, lane);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) Dq = fmaf((float)gf[kk][e], (float)of[e], Dq);
-    }
   }
-  Dq += __shfl_xor(Dq, 32, 64);
-  if (qok && h == 0) a.delta[((long)bi * a.A + hh) * a.s + qrow] = Dq;
   f32x16 dq[2] = {zero16(), zero16()};  // rows d, column = the lane's query
   const int nkb = a.s / 64;
   Block64 kblk, vblk;
@@ -514,6 +512,12 @@ __global__ __launch_bounds__(256) void attn_dq_mfma(AttnArgs a, float scale2, fl
   }
 }
 
+// both roles in one launch: grid.z = 0 the dq workgroups, 1 the dk/dv workgroups
+__global__ __launch_bounds__(256, 2) void attn_bwd_mfma(AttnArgs a, float scale2, float scale) {
+  if (blockIdx.z == 0) attn_dq_body(a, scale2, scale);
+  else attn_dkdv_body(a, scale2, scale);
+}
+
 // ------------------------------------------------------------------ launchers
 static bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
@@ -540,12 +544,14 @@ hipError_t launch_attn_bwd(Dtype dt, const AttnArgs& a, hipStream_t st) {
   float scale = 1.0f / sqrtf((float)a.d), scale2 = LOG2E * scale;
   hipError_t e;
   if (attn_uses_mfma(dt, a)) {
-    // dq first: it also writes delta, which dk/dv reads
-    dim3 grid((a.s + 127) / 128, a.b * a.A);
-    hipLaunchKernelGGL(attn_dq_mfma, grid, dim3(256), 0, st, a, scale2, scale);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_dkdv_mfma, grid, dim3(256), 0, st, a, scale2, scale);
+    if (!a.delta_blocks) {  // no product in front that left delta behind
+      long nd = (long)a.b * a.s * a.A;
+      hipLaunchKernelGGL(attn_delta_kernel<bf16>, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, st, a);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    dim3 grid((a.s + 127) / 128, a.b * a.A, 2);
+    hipLaunchKernelGGL(attn_bwd_mfma, grid, dim3(256), 0, st, a, scale2, scale);
     return hipGetLastError();
   }
   long nd = (long)a.b * a.s * a.A;

@@ -239,6 +239,19 @@ struct FragAddr {
   }
 };
 
+// sum over each group of 8 consecutive lanes, in every lane of the group, as a fixed tree: lane pairs, pairs of
+// pairs (both inside a quad), then the two quads (the mirror image within the half row) -- cross-lane operands of
+// the adds themselves, no trip through LDS
+__device__ __forceinline__ float sum8(float v) {
+  auto dpp = [](float x, auto CTRL) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(CTRL)::value, 0xF, 0xF, true));
+  };
+  v += dpp(v, std::integral_constant<int, 0xB1>{});   // quad_perm [1,0,3,2]
+  v += dpp(v, std::integral_constant<int, 0x4E>{});   // quad_perm [2,3,0,1]
+  v += dpp(v, std::integral_constant<int, 0x141>{});  // row_half_mirror
+  return v;
+}
+
 template <int BM, int BN, int WGM, int WGN, int NS, bool AKS, bool BKS, int BK>
 struct GemmTile {
   static constexpr int NW = WGM * WGN, NT = 64 * NW;
@@ -537,7 +550,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
     }
   };
   if constexpr (PRE) {
-    if (epi & (EPI_ADD | EPI_MUL)) {
+    if (epi & (EPI_ADD | EPI_MUL | EPI_ROWDOT)) {
 #pragma unroll
       for (int i = 0; i < MI; ++i) load_aux_block(i, pre[i]);
     }
@@ -591,7 +604,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
               t[u].x += (float)bv[0]; t[u].y += (float)bv[1]; t[u].z += (float)bv[2]; t[u].w += (float)bv[3];
             }
         }
-        if (epi & (EPI_ADD | EPI_MUL)) {
+        if (epi & (EPI_ADD | EPI_MUL | EPI_ROWDOT)) {
           float4 xv[HB];
 #pragma unroll
           for (int u = 0; u < HB; ++u) {
@@ -615,12 +628,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g, i
               }
             }
           }
+          if (epi & EPI_ROWDOT) {
+            // a row's 32 columns of a block sit in 8 consecutive lanes (4 columns each): products of the
+            // outputs as they are stored, summed over the lane's four, then over the eight lanes in a fixed tree
 #pragma unroll
-          for (int u = 0; u < HB; ++u) {
-            if (epi & EPI_ADD) {
-              t[u].x += xv[u].x; t[u].y += xv[u].y; t[u].z += xv[u].z; t[u].w += xv[u].w;
-            } else {
-              t[u].x *= xv[u].x; t[u].y *= xv[u].y; t[u].z *= xv[u].z; t[u].w *= xv[u].w;
+            for (int u = 0; u < HB; ++u) {
+              const bool ok = FULL || (rows[u] < g.M && cols[u] < g.N);
+              float part = (float)(bf16)t[u].x * xv[u].x + (float)(bf16)t[u].y * xv[u].y +
+                           (float)(bf16)t[u].z * xv[u].z + (float)(bf16)t[u].w * xv[u].w;
+              part = ok ? part : 0.f;
+              part = sum8(part);
+              if (ok && (lane & 7) == 0) g.rowdot[(long)(cols[u] >> 5) * g.M + rows[u]] = part;
+            }
+          } else {
+#pragma unroll
+            for (int u = 0; u < HB; ++u) {
+              if (epi & EPI_ADD) {
+                t[u].x += xv[u].x; t[u].y += xv[u].y; t[u].z += xv[u].z; t[u].w += xv[u].w;
+              } else {
+                t[u].x *= xv[u].x; t[u].y *= xv[u].y; t[u].z *= xv[u].z; t[u].w *= xv[u].w;
+              }
             }
           }
         }
@@ -752,7 +779,10 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
     if (a_ext > 0x7fffffffL - 4096 || b_ext > 0x7fffffffL - 4096) return false;
     if ((long)BK * g.lda * 2 > 0x7fffffffL || (long)BK * g.ldb * 2 > 0x7fffffffL) return false;
   }
-  if ((g.epi & (EPI_ADD | EPI_MUL)) && (g.ldaux % 4 || !aligned_to(g.aux, 16))) return false;
+  if ((g.epi & (EPI_ADD | EPI_MUL | EPI_ROWDOT)) && (g.ldaux % 4 || !aligned_to(g.aux, 16))) return false;
+  if ((g.epi & EPI_ROWDOT) && ((g.epi & (EPI_ADD | EPI_MUL | EPI_GELU | EPI_ACC32 | EPI_OUT32)) || g.batch != 1 ||
+                               !g.rowdot || !g.aux || !aligned_to(g.rowdot, 4)))
+    return false;
   if ((g.epi & EPI_BIAS) && !aligned_to(g.bias, 8)) return false;
   if ((g.epi & EPI_GELU) && !aligned_to(g.C2, 8)) return false;
   if ((g.epi & EPI_BSUM) && !(g.a_kstrided && g.b_kstrided && g.batch <= 4)) return false;
@@ -761,7 +791,9 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g) {
 
 hipError_t launch_gemm(Dtype dt, const GemmArgs& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;
-  if (gemm_uses_mfma(dt, g)) {
+  const bool mfma = gemm_uses_mfma(dt, g);
+  if ((g.epi & EPI_ROWDOT) && !mfma) return hipErrorInvalidValue;  // only the MFMA kernel's epilogue has it
+  if (mfma) {
     const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch;
     const long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
     const bool tt = g.a_kstrided && g.b_kstrided;   // the weight-gradient layout

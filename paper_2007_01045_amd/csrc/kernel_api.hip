@@ -50,6 +50,11 @@ int dapple_gemm(int dtype, const dapple_gemm_desc* d, void* stream) {
     if (!d->bsum) return STAGE_E_NULL;
     if (!d->a_kstrided || !d->b_kstrided || d->batch > 1) return STAGE_E_CONFIG;
   }
+  if (d->epi & DAPPLE_EPI_ROWDOT) {
+    if (!d->rowdot || !d->aux) return STAGE_E_NULL;
+    if ((d->epi & (DAPPLE_EPI_ADD | DAPPLE_EPI_MUL | DAPPLE_EPI_GELU | DAPPLE_EPI_ACC32 | DAPPLE_EPI_OUT32)) || d->batch > 1)
+      return STAGE_E_CONFIG;
+  }
   GemmArgs g{};
   g.A = d->A; g.B = d->B; g.C = d->C; g.C2 = d->C2; g.bias = d->bias; g.aux = d->aux;
   g.M = d->M; g.N = d->N; g.K = d->K; g.lda = d->lda; g.ldb = d->ldb; g.ldc = d->ldc; g.ldaux = d->ldaux;
@@ -60,7 +65,9 @@ int dapple_gemm(int dtype, const dapple_gemm_desc* d, void* stream) {
   g.m_valid = d->M; g.n_valid = d->N; g.bsum_z[0] = d->bsum;
   if (g.K % g.kseg_len) return STAGE_E_CONFIG;
   Dtype dt = dtype == STAGE_DTYPE_BF16 ? DT_BF16 : DT_F32;
+  g.rowdot = d->rowdot;
   int mfma = gemm_uses_mfma(dt, g) ? 1 : 0;
+  if ((g.epi & EPI_ROWDOT) && !mfma) return STAGE_E_CONFIG;  // the plain kernel has no such epilogue
   hipError_t e = launch_gemm(dt, g, (hipStream_t)stream);
   return e == hipSuccess ? mfma : STAGE_E_DEVICE;
 }

@@ -24,7 +24,11 @@ enum GemmEpi {
   EPI_ACC32 = 16,  // C is fp32 and C += t (weight-gradient accumulation)
   EPI_OUT32 = 32,  // C is fp32 and C = t
   EPI_AUX32 = 64,  // aux is fp32 (residual stream of a bf16 stage)
-  EPI_BSUM = 128   // bsum[n] += sum_k B(n,k): the bias gradient rides along with the weight gradient
+  EPI_BSUM = 128,  // bsum[n] += sum_k B(n,k): the bias gradient rides along with the weight gradient
+  // rowdot[j*M + m] = sum over the 32 columns n of block j of C[m,n] (as stored, rounded to bf16) * aux[m,n];
+  // aux is neither added nor multiplied in.  MFMA kernel only, bf16 output, batch 1.  (The attention
+  // backward's delta = rowsum(dctx o ctx) per head leaves the product that makes dctx this way.)
+  EPI_ROWDOT = 256
 };
 
 struct GemmArgs {
@@ -49,6 +53,7 @@ struct GemmArgs {
   void* Cz[4];
   // EPI_BSUM: fp32 [N] per instance (a NULL entry skips that instance); both operands k-strided
   float* bsum_z[4];
+  float* rowdot;  // EPI_ROWDOT: fp32 [ceil(N/32)][M]
   int k_valid;  // k-strided operands: rows k >= k_valid read as zero (K itself is padded)
   int m_valid, n_valid;  // rows of A / B that exist in memory (0 = M / N); rows beyond read as zero
   int epi;
@@ -63,6 +68,9 @@ bool gemm_uses_mfma(Dtype dt, const GemmArgs& g);
 // q,k,v,ctx,dq,dk,dv,dctx: [b*s, H] row-major, head h in columns [h*d, (h+1)*d).
 // lse: [b, A, s] fp32, log2-domain logsumexp of the scaled logits.
 // delta: [b, A, s] fp32 scratch, rowsum(dctx * ctx) per head.
+// delta_blocks (may be NULL): fp32 [H/32][b*s], the same sums per block of 32 columns as EPI_ROWDOT
+// of the product that made dctx leaves them; when set, the MFMA backward reads delta from there
+// (a head's d/32 blocks added in ascending order) and `delta` is not touched.
 // ctx32 (may be NULL): unrounded fp32 copy of ctx, written by the forward and used by the
 // backward for delta -- an error in delta shifts a whole row of dS coherently, so a bf16 ctx
 // there costs percents of accuracy in dq and dk although ctx itself is accurate to 2^-9.
@@ -74,6 +82,7 @@ struct AttnArgs {
   const void* dctx;
   void *dq, *dk, *dv;
   float* delta;
+  const float* delta_blocks;
   int b, s, A, d, H;
 };
 hipError_t launch_attn_fwd(Dtype dt, const AttnArgs& a, hipStream_t st);

@@ -181,7 +181,8 @@ void build_layout(const stage_config& c, Layout& L) {
   size_t wo = 0;
   auto wtake = [&](size_t bytes) { size_t o = wo; wo += align_up(bytes); return o; };
   L.ws_dx[0] = wtake(U); L.ws_dx[1] = wtake(U); L.ws_dy1 = wtake(U); L.ws_dctx = wtake(U);
-  L.ws_delta = wtake((size_t)c.micro_batch * c.n_heads * c.seq * 4);
+  // delta of the attention backward: [b, A, s], or one row sum per block of 32 columns, [ceil(H/32)][T]
+  L.ws_delta = wtake(std::max((size_t)c.micro_batch * c.n_heads * c.seq, (size_t)((c.hidden + 31) / 32) * T) * 4);
   if (c.dtype == STAGE_DTYPE_BF16) {
     for (int fs = 0; fs < (L.recompute ? 2 : 1); ++fs) {
       L.ws_y1f[fs] = wtake(T * H * 4); L.ws_yf[fs][0] = wtake(T * H * 4); L.ws_yf[fs][1] = wtake(T * H * 4);
@@ -553,17 +554,27 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
     TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dy1, z1, dt == DT_BF16, st1, w(p.ln1g), dz1, part_ln1, &nblk, T, H, q); }));
     TRY(fork(l, 2));
     const int nblk_ln1 = nblk;
-    {  // dctx = dz1 Wo^T
+    AttnArgs aa{};
+    aa.q = qkv; aa.k = qkv + U; aa.v = qkv + 2 * U; aa.ctx = ctx; aa.lse = lse; aa.dctx = dctx;
+    aa.ctx32 = dt == DT_BF16 ? (float*)(sl + a.ctx32) : nullptr;
+    aa.dq = dqkv; aa.dk = dqkv + U; aa.dv = dqkv + 2 * U; aa.delta = delta;
+    aa.b = cfg.micro_batch; aa.s = cfg.seq; aa.A = cfg.n_heads; aa.d = H / cfg.n_heads; aa.H = H;
+    {  // dctx = dz1 Wo^T; where the MFMA kernels run, its epilogue also leaves rowsum(dctx o ctx) per block of
+       // 32 columns, the delta of the attention backward
       GemmArgs ga{};
       ga.A = dz1; ga.lda = H; ga.B = w(p.Wo); ga.ldb = H; ga.C = dctx; ga.ldc = H; ga.M = T; ga.N = H; ga.K = H;
+      if (aa.ctx32 && attn_uses_mfma(dt, aa)) {
+        GemmArgs probe = ga;
+        probe.epi = EPI_ROWDOT | EPI_AUX32; probe.aux = aa.ctx32; probe.ldaux = H; probe.rowdot = delta;
+        probe.batch = 1; probe.kseg_len = ga.K; probe.k_valid = ga.K; probe.m_valid = ga.M; probe.n_valid = ga.N;
+        if (gemm_uses_mfma(dt, probe)) {
+          ga = probe;
+          aa.delta_blocks = delta;
+        }
+      }
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
     {
-      AttnArgs aa{};
-      aa.q = qkv; aa.k = qkv + U; aa.v = qkv + 2 * U; aa.ctx = ctx; aa.lse = lse; aa.dctx = dctx;
-      aa.ctx32 = dt == DT_BF16 ? (float*)(sl + a.ctx32) : nullptr;
-      aa.dq = dqkv; aa.dk = dqkv + U; aa.dv = dqkv + 2 * U; aa.delta = delta;
-      aa.b = cfg.micro_batch; aa.s = cfg.seq; aa.A = cfg.n_heads; aa.d = H / cfg.n_heads; aa.H = H;
       double fl = 8.0 * T * (double)cfg.seq * H;
       TRY(run(KC_ATTN_BWD, fl, [&](hipStream_t q) { return launch_attn_bwd(dt, aa, q); }));
     }

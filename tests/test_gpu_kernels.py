@@ -35,7 +35,7 @@ def gemm_case(dtype, M, N, K, akS, bkS, epi, batch=1, nseg=1, expect_mfma=None, 
     A = rnd("A", (batch, nseg, M, ks), bf16=bf)
     Bm = rnd("B", (batch, nseg, N, ks), bf16=bf)
     bias = rnd("bias", (batch, N), bf16=bf)
-    aux = rnd("aux", (batch, M, N), bf16=bf)
+    aux = rnd("aux", (batch, M, N), bf16=bf and not (epi & B.EPI_AUX32))
     C0 = rnd("C0", (batch, M, N), bf16=False)
     acc = np.stack([sum(A[z, i] @ Bm[z, i].T for i in range(nseg)) for z in range(batch)])
     t = acc.copy()
@@ -48,7 +48,7 @@ def gemm_case(dtype, M, N, K, akS, bkS, epi, batch=1, nseg=1, expect_mfma=None, 
     A_mem = A.transpose(0, 1, 3, 2) if akS else A        # k-strided: [k][rows]
     B_mem = Bm.transpose(0, 1, 3, 2) if bkS else Bm
     dA, dB = dev(A_mem, td), dev(B_mem, td)
-    dbias, daux = dev(bias, td), dev(aux, td)
+    dbias, daux = dev(bias, td), dev(aux, torch.float32 if epi & B.EPI_AUX32 else td)
     d = B.dapple_gemm_desc()
     d.A, d.B, d.bias, d.aux = dA.data_ptr(), dB.data_ptr(), dbias.data_ptr(), daux.data_ptr()
     d.M, d.N, d.K = M, N, K
@@ -74,10 +74,22 @@ def gemm_case(dtype, M, N, K, akS, bkS, epi, batch=1, nseg=1, expect_mfma=None, 
         bs0 = rnd("bs0", (N,), bf16=False)
         dbs = dev(bs0, torch.float32)
         d.bsum = dbs.data_ptr()
+    if epi & B.EPI_ROWDOT:        # per row and block of 32 columns: sum of (stored output) * aux
+        nblk = (N + 31) // 32
+        drd = torch.full((nblk, M), float("nan"), dtype=torch.float32, device="cuda")
+        d.rowdot = drd.data_ptr()
     used = B.dapple_gemm(dtype, d)
     torch.cuda.synchronize()
     if expect_mfma is not None:
         assert used == int(expect_mfma)
+    if epi & B.EPI_ROWDOT:
+        stored = to_np(dC)[0].astype(np.float64)
+        prod = stored * aux[0].astype(np.float64)
+        want_rd = np.stack([prod[:, 32 * j:32 * j + 32].sum(axis=1) for j in range(nblk)])
+        got_rd = to_np(drd)
+        assert np.isfinite(got_rd).all(), "a row sum was not written"
+        assert rel_l2(got_rd, want_rd) < 1e-5, (M, N, K, rel_l2(got_rd, want_rd))
+        assert np.abs(got_rd - want_rd).max() < 1e-4 * max(np.abs(want_rd).max(), 1.0)
     if epi & B.EPI_BSUM:
         want_bs = bs0 + sum(Bm[0, i].sum(axis=1) for i in range(nseg))
         assert rel_l2(to_np(dbs), want_bs) < (1e-5 if bf else 2e-5), (M, N, K, rel_l2(to_np(dbs), want_bs))
@@ -107,6 +119,34 @@ def test_gemm_weight_gradient_with_bias_column_sums(tile):
     for (M, N, K) in ((264, 136, 64), (264, 136, 320), (1024, 2048 + 8, 2048), (72, 40, 192)):
         gemm_case(B.DTYPE_BF16, M, N, K, True, True, B.EPI_ACC32 | B.EPI_BSUM, expect_mfma=True, tile=tile)
     gemm_case(B.DTYPE_F32, 70, 52, 33, True, True, B.EPI_ACC32 | B.EPI_BSUM, expect_mfma=False, tile=tile)
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 6])
+def test_gemm_row_sums_of_output_times_second_operand(tile):
+    # ragged M and N (N not a multiple of 32: the last block is short), bf16 and fp32 second operand
+    gemm_case(B.DTYPE_BF16, 328, 200, 192, False, False, B.EPI_ROWDOT | B.EPI_AUX32, expect_mfma=True, tile=tile)
+    gemm_case(B.DTYPE_BF16, 264, 136, 320, False, True, B.EPI_ROWDOT | B.EPI_BIAS, expect_mfma=True, tile=tile)
+    gemm_case(B.DTYPE_BF16, 512, 256, 128, False, False, B.EPI_ROWDOT | B.EPI_AUX32, expect_mfma=True, tile=tile)
+
+
+def test_gemm_row_sums_need_the_mfma_kernel():
+    d = B.dapple_gemm_desc()
+    x = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
+    d.A = d.B = d.C = d.aux = d.rowdot = x.data_ptr()
+    d.M = d.N = d.K = 48
+    d.lda = d.ldb = d.ldc = d.ldaux = 48
+    def code(dtype):
+        with pytest.raises(B.StageError) as e:
+            B.dapple_gemm(dtype, d)
+        return e.value.code
+    d.epi = B.EPI_ROWDOT
+    assert code(B.DTYPE_F32) == B.STAGE_E_CONFIG          # fp32: the plain kernel
+    assert code(B.DTYPE_BF16) == B.STAGE_E_CONFIG         # K = 48: the plain kernel
+    d.epi = B.EPI_ROWDOT | B.EPI_ADD
+    assert code(B.DTYPE_BF16) == B.STAGE_E_CONFIG         # nothing else may use aux
+    d.epi = B.EPI_ROWDOT
+    d.rowdot = None
+    assert code(B.DTYPE_BF16) == B.STAGE_E_NULL
 
 
 @pytest.mark.parametrize("akS", [False, True])
