@@ -519,25 +519,27 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
 
     // y = LN(z2): dz2, and block partial sums for the gradients of ln2 gain/shift and of b2
     TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dyin, z2, dt == DT_BF16, st2, w(p.ln2g), dz2, part_ln2, &nblk, T, H, q); }));
-    TRY(fork(l, 0));
     // One side stream: the layer's bias and LayerNorm-parameter reductions wait and go out as ONE
     // launch after the last weight-gradient product (the side stream is the longest chain of a
     // step, and a small kernel costs it a dispatch of ~15 us when the GPU is full).  Each
     // reduction adds in the same order as the stand-alone kernels.
     const int nblk_ln2 = nblk;
-    {  // dW2 += g^T dz2
-      GemmArgs ga{};
-      ga.A = g; ga.lda = F; ga.a_kstrided = 1; ga.B = dz2; ga.ldb = H; ga.b_kstrided = 1;
-      ga.C = gr(p.W2); ga.ldc = H; ga.M = F; ga.N = H; ga.K = T; ga.epi = EPI_ACC32;
-      TRY(gemm(KC_GEMM_WGRAD, ga, true));
-    }
     {  // du = (dz2 W2^T) o GELU'(u)
       GemmArgs ga{};
       ga.A = dz2; ga.lda = H; ga.B = w(p.W2); ga.ldb = H; ga.aux = gp; ga.ldaux = F;
       ga.C = du; ga.ldc = F; ga.M = T; ga.N = F; ga.K = H; ga.epi = EPI_MUL;
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
+    // two forks per layer (here and after the attention backward), not one per side launch: every event
+    // recorded on this stream sits between two kernels of the task's chain (14.17 -> 14.14 ms; a single fork per
+    // layer holds the side stream back too long: 14.35)
     TRY(fork(l, 1));
+    {  // dW2 += g^T dz2
+      GemmArgs ga{};
+      ga.A = g; ga.lda = F; ga.a_kstrided = 1; ga.B = dz2; ga.ldb = H; ga.b_kstrided = 1;
+      ga.C = gr(p.W2); ga.ldc = H; ga.M = F; ga.N = H; ga.K = T; ga.epi = EPI_ACC32;
+      TRY(gemm(KC_GEMM_WGRAD, ga, true));
+    }
     {  // dW1 += y1^T du, and db1 += the column sums of du in the same launch
       GemmArgs ga{};
       ga.A = y1; ga.lda = H; ga.a_kstrided = 1; ga.B = du; ga.ldb = F; ga.b_kstrided = 1;
@@ -552,7 +554,6 @@ int dapple_stage::backward(char* sl, const void* dy, void* dx) {
       TRY(gemm(KC_GEMM_DGRAD, ga));
     }
     TRY(run(KC_LN_BWD, 0, [&](hipStream_t q) { return launch_ln_bwd(dt, dy1, z1, dt == DT_BF16, st1, w(p.ln1g), dz1, part_ln1, &nblk, T, H, q); }));
-    TRY(fork(l, 2));
     const int nblk_ln1 = nblk;
     AttnArgs aa{};
     aa.q = qkv; aa.k = qkv + U; aa.v = qkv + 2 * U; aa.ctx = ctx; aa.lse = lse; aa.dctx = dctx;
