@@ -1,5 +1,6 @@
 // Device-side helpers shared by the gfx950 kernels.
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -59,11 +60,26 @@ __device__ __forceinline__ bf16x8 join8(bf16x4 lo, bf16x4 hi) {
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-// wave-wide sum (64 lanes), result in every lane
+// wave-wide sum (64 lanes), result in every lane, in a fixed order: inside each row of 16 lanes a tree of four
+// steps whose cross-lane operand is part of the add itself (lane pairs, pairs of pairs, the two quads of a half
+// row by its mirror image, the two half rows by the row's mirror image), then the four row totals in ascending
+// order through scalar registers.  No trip through the LDS crossbar: six dependent ds_bpermute round trips took
+// longer than the rest of a LayerNorm row's arithmetic.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  auto step = [](float x, auto CTRL) {
+    return x + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(CTRL)::value,
+                                                                     0xF, 0xF, true));
+  };
+  v = step(v, std::integral_constant<int, 0xB1>{});   // quad_perm [1,0,3,2]
+  v = step(v, std::integral_constant<int, 0x4E>{});   // quad_perm [2,3,0,1]
+  v = step(v, std::integral_constant<int, 0x141>{});  // row_half_mirror
+  v = step(v, std::integral_constant<int, 0x140>{});  // row_mirror
+  const int b = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+  return ((r0 + r1) + r2) + r3;
 }
 
 }  // namespace dapple
